@@ -1,0 +1,432 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something that is NOT the
+oracle -- a dense Hadamard matrix built from popcounts, numpy's own float16, closed forms and
+identities the paper states, brute force on tiny inputs.  No GPU involved."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2603_27914_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def dense_hu():
+    """H_u[k][j] = (-1)^<k,j> with <k,j> the inner product of the binary digits (Thm 1, proof)."""
+    k = np.arange(256)
+    pc = np.array([bin(v).count("1") for v in range(256)])
+    return (1 - 2 * (pc[k[:, None] & k[None, :]] & 1)).astype(np.int64)
+
+
+def sylvester(n):
+    """The recursion of Sec. 2.3 without the normalisation: H_1=[1], H_2n=[[H,H],[H,-H]]."""
+    H = np.array([[1]], dtype=np.int64)
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+def np_f16(word):
+    return float(np.array([word & 0xFFFF], dtype=np.uint16).view(np.float16)[0])
+
+
+def unpack_numpy(codes, scales, N, K):
+    """Second implementation of the storage layout, written from its description alone.
+    -> (c int64 [N,K], d float64 [N,KB], z float64 [N,KB])."""
+    KB, NT = K // 256, (N + 15) // 16
+    t = codes.reshape(NT, KB, 384)
+    e = np.arange(256)
+    lane_g, i = e >> 6, e & 63
+    c = np.zeros((NT * 16, K), dtype=np.int64)
+    for r in range(16):
+        lane = 16 * lane_g + r
+        lo = (t[:, :, 4 * lane + (i >> 4)] >> (2 * (i & 15)).astype(np.uint32)) & 3
+        hi = (t[:, :, 256 + 2 * lane + (i >> 5)] >> (i & 31).astype(np.uint32)) & 1
+        c[r::16, :] = (lo | (hi << 2)).reshape(NT, K)
+    s = scales.reshape(NT, KB, 16).transpose(0, 2, 1).reshape(NT * 16, KB)
+    d = (s & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float64)
+    z = (s >> 16).astype(np.uint16).view(np.float16).astype(np.float64)
+    return c[:N], d[:N], z[:N]
+
+
+# ------------------------------------------------------------------------------ transform pins
+
+
+def test_golden_constants(ref):
+    g = json.load(open(os.path.join(GOLDEN, "paper_constants.json")))
+    assert ref.t_star() == g["t_star"]["value"]
+    assert g["normalisation"]["value"] == 1.0 / np.sqrt(256.0) == 0.0625
+    # byte budget of Sec. 4.1: 96 + 2 + 2 bytes per 256 weights
+    assert ref.lib().itq3s_ref_codes_bytes(16, 256) == 16 * g["quant_bytes"]["value"]
+    assert ref.lib().itq3s_ref_scales_bytes(16, 256) == 16 * (g["scale_bytes"]["value"] + g["zero_point_bytes"]["value"])
+    per_block = (ref.lib().itq3s_ref_codes_bytes(4096, 4096) + ref.lib().itq3s_ref_scales_bytes(4096, 4096)) / (4096 * 16)
+    assert per_block == g["block_bytes"]["value"] and per_block * 8 / 256 == g["bits_per_weight"]["value"]
+
+
+def test_hu_squared_is_256_identity():
+    H = dense_hu()
+    assert np.array_equal(H @ H, 256 * np.eye(256, dtype=np.int64))
+    assert np.array_equal(H, H.T)
+
+
+def test_butterfly_equals_entry_formula_equals_recursion(ref):
+    H = dense_hu()
+    assert np.array_equal(H, sylvester(256))
+    for j in range(256):
+        e = np.zeros(256)
+        e[j] = 1.0
+        assert np.array_equal(ref.fwht256(e), H[:, j].astype(np.float64)), j
+
+
+def test_butterfly_matches_dense_on_integers(ref):
+    rng = np.random.default_rng(1)
+    H = dense_hu()
+    for _ in range(20):
+        a = rng.integers(-1000, 1000, size=256)
+        assert np.array_equal(ref.fwht256(a.astype(np.float64)), (H @ a).astype(np.float64))
+
+
+def test_butterfly_stage_order(ref):
+    """The association order of the additions is part of the quantizer's definition: rebuild the
+    network here with explicit python loops in the printed stage order 1,2,4,...,128."""
+    rng = np.random.default_rng(2)
+    a = rng.standard_normal(256) * np.exp(3 * rng.standard_normal(256))
+    b = a.copy()
+    step = 1
+    while step < 256:
+        for i in range(256):
+            if i & step == 0:
+                u, v = b[i], b[i + step]
+                b[i], b[i + step] = u + v, u - v
+        step *= 2
+    assert np.array_equal(ref.fwht256(a), b)
+    # a different stage order gives the same value only up to rounding -- and not the same bits
+    c = a.copy()
+    step = 128
+    while step >= 1:
+        for i in range(256):
+            if i & step == 0:
+                u, v = c[i], c[i + step]
+                c[i], c[i + step] = u + v, u - v
+        step //= 2
+    assert np.allclose(b, c, rtol=0, atol=1e-10 * np.abs(a).sum())
+
+
+def test_round_trip(ref):
+    rng = np.random.default_rng(3)
+    a = rng.integers(-(2**20), 2**20, size=256).astype(np.float64)
+    assert np.array_equal(ref.fwht256(ref.fwht256(a)) / 256.0, a)  # integers: exact
+    x = rng.standard_normal(256)
+    back = ref.fwht256(ref.fwht256(x)) / 256.0
+    assert np.max(np.abs(back - x)) <= 64 * np.finfo(np.float64).eps * np.max(np.abs(x))
+
+
+def test_isometry_and_spike(ref):
+    rng = np.random.default_rng(4)
+    w = rng.standard_normal(256).astype(np.float32)
+    wt = ref.forward_block(w)
+    assert abs(np.linalg.norm(wt) - np.linalg.norm(w.astype(np.float64))) < 1e-12 * np.linalg.norm(wt)
+    # Sec. 3.1: a single outlier M contributes M / sqrt(n) to every coefficient
+    for j in (0, 1, 77, 255):
+        s = np.zeros(256, dtype=np.float32)
+        s[j] = 48.0
+        assert np.array_equal(np.abs(ref.forward_block(s)), np.full(256, 3.0))
+    # H 1 = 16 e_0, hence mean(w') = w_0 / 16
+    ones = ref.forward_block(np.ones(256, dtype=np.float32))
+    assert ones[0] == 16.0 and not ones[1:].any()
+    assert abs(wt.mean() - float(w[0]) / 16.0) < 1e-14
+    # Cor. 1: ||H w||_inf <= ||w||_1 / sqrt(n)
+    assert np.abs(wt).max() <= np.abs(w.astype(np.float64)).sum() / 16.0 + 1e-12
+
+
+# ------------------------------------------------------------------------------ fp16 conversion
+
+
+def test_fp16_conversion_matches_numpy(ref):
+    rng = np.random.default_rng(5)
+    vals = np.concatenate(
+        [
+            rng.standard_normal(2000).astype(np.float32) * np.float32(10.0) ** rng.integers(-9, 6, 2000).astype(np.float32),
+            np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e-8, 5.96e-8, 2.98e-8, 2.9802322e-8, 2.9802326e-8, 6.1e-5, 6.0975e-5, 1.0, 1.00048828125, 1.0009765625, 1.00146484375], dtype=np.float32),
+        ]
+    )
+    for v in vals:
+        want = int(np.array([v], dtype=np.float32).astype(np.float16).view(np.uint16)[0])
+        assert ref.f32_to_f16_bits(float(v)) == want, v
+    for h in range(0, 65536, 7):
+        got, want = ref.f16_bits_to_f64(h), float(np.array([h], dtype=np.uint16).view(np.float16)[0])
+        assert (np.isnan(got) and np.isnan(want)) or got == want
+
+
+# ------------------------------------------------------------------------------ quantizer pins
+
+
+def independent_quantize_block(w):
+    """Def. 1 / Alg. 1 re-done with a dense matrix in extended precision.  Returns the real-valued
+    quantities; comparisons against the oracle allow for this routine's own rounding."""
+    H = dense_hu().astype(np.longdouble)
+    wt = (H @ w.astype(np.longdouble)) / np.longdouble(16)
+    mu = wt.mean()
+    sigma = np.sqrt(((wt - mu) ** 2).mean())
+    return wt, mu, sigma
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_quantize_block_against_definition(ref, seed):
+    rng = np.random.default_rng(100 + seed)
+    w = (0.02 * rng.standard_t(4.0, size=256)).astype(np.float32)
+    if seed % 2:
+        w[0] = np.float32(0.9)  # big first element -> non-zero mean in the transform domain -> z != 0
+    codes, word, flags = ref.quantize_block(w)
+    assert flags == 0
+    wt, mu, sigma = independent_quantize_block(w)
+    d_hat = np_f16(word)
+    z = np_f16(word >> 16)
+    # scale: T* sigma rounded to fp16 (exact match unless within 1e-9 of a rounding boundary)
+    want_d = float(np.float16(np.float32(0.7979 * float(sigma))))
+    assert d_hat == want_d
+    assert z == -np.floor(float(mu) / d_hat + 0.5) and z == int(z)
+    if seed % 2:
+        assert z != 0
+    # codes: literal Def. 1 formula wherever it is not within rounding of a decision point
+    x = wt / np.longdouble(d_hat) + np.longdouble(z) + np.longdouble(0.5)
+    q = np.clip(np.floor(x), -1, 1).astype(np.int64)
+    safe = np.abs(x - np.round(x)) > 1e-9
+    assert safe.sum() >= 250
+    assert np.array_equal(codes.astype(np.int64)[safe] - 1, q[safe])
+    assert set(np.unique(codes)) <= {0, 1, 2}
+
+
+def test_quantize_threshold_ties(ref):
+    """Half-up rounding of Def. 1: a coefficient exactly on (0.5 - z) d goes to +1, one exactly on
+    (-0.5 - z) d stays 0.  Built in the transform domain with integer-valued data so that the
+    forward butterflies are exact."""
+    rng = np.random.default_rng(7)
+    for trial in range(200):
+        target = rng.integers(-40, 41, size=256).astype(np.float64) * 16.0  # w' * 16, all multiples of 16
+        w = ref.fwht256(target) / 256.0  # exact: sums of multiples of 16, divided by 256
+        assert np.array_equal(w, w.astype(np.float32).astype(np.float64))
+        codes, word, flags = ref.quantize_block(w.astype(np.float32))
+        wt = ref.forward_block(w.astype(np.float32))
+        assert np.array_equal(wt * 16.0, target)
+        d, z = np_f16(word), np_f16(word >> 16)
+        assert d > 0
+        want = np.where(wt >= (0.5 - z) * d, 2, np.where(wt < (-0.5 - z) * d, 0, 1))
+        assert np.array_equal(codes, want)
+    # an explicit tie: choose w' so that one coefficient equals exactly 0.5 d and one exactly -0.5 d
+    wt = np.zeros(256)
+    wt[1::2] = 8.0
+    wt[0::2] = -8.0
+    w = (ref.fwht256(wt * 16.0) / 256.0).astype(np.float32)
+    codes, word, _ = ref.quantize_block(w)
+    d = np_f16(word)
+    wt2 = wt.copy()
+    wt2[10], wt2[11] = 0.5 * d, -0.5 * d  # d is fp16: halves are exact
+    w2 = ref.fwht256(wt2 * 16.0) / 256.0
+    if np.array_equal(w2, w2.astype(np.float32).astype(np.float64)):
+        codes2, word2, _ = ref.quantize_block(w2.astype(np.float32))
+        d2, z2 = np_f16(word2), np_f16(word2 >> 16)
+        wt3 = ref.forward_block(w2.astype(np.float32))
+        for j in range(256):
+            if wt3[j] == (0.5 - z2) * d2:
+                assert codes2[j] == 2
+            if wt3[j] == (-0.5 - z2) * d2:
+                assert codes2[j] == 1
+
+
+def test_degenerate_blocks(ref):
+    # all-zero and transform-domain-constant blocks: sigma = 0 -> scale 0, every digit 0
+    for w in (np.zeros(256, np.float32), np.eye(1, 256, 0, dtype=np.float32)[0] * 3):
+        codes, word, flags = ref.quantize_block(w)
+        assert word == 0 and flags == 0 and np.all(codes == 1)
+    # scale below the fp16 range
+    codes, word, flags = ref.quantize_block(np.full(256, 1e-12, np.float32) * np.arange(256, dtype=np.float32))
+    assert word == 0 and np.all(codes == 1)
+    # non-finite input is flagged and stored as zero
+    w = np.ones(256, np.float32)
+    w[5] = np.inf
+    codes, word, flags = ref.quantize_block(w)
+    assert word == 0 and flags & ref.FLAG_NONFINITE and np.all(codes == 1)
+    # scale above the fp16 range saturates
+    rng = np.random.default_rng(8)
+    codes, word, flags = ref.quantize_block((rng.standard_normal(256) * 1e6).astype(np.float32))
+    assert (word & 0xFFFF) == 0x7BFF and flags & ref.FLAG_SCALE_SAT
+    # zero-point clamp
+    w = (rng.standard_normal(256) * 1e-3).astype(np.float32)
+    w[0] = 1e3
+    codes, word, flags = ref.quantize_block(w)
+    assert abs(np_f16(word >> 16)) == 2048 and flags & ref.FLAG_Z_CLAMP
+
+
+def test_gaussian_block_statistics(ref):
+    """For Gaussian data the scale is T* sigma and the zero digit covers |x| < d/2 = 0.399 sigma,
+    i.e. a fraction erf(0.399/sqrt 2) = 0.310 of the coefficients (Sec. 3.3)."""
+    from math import erf, sqrt
+
+    rng = np.random.default_rng(9)
+    zeros, ratio = [], []
+    for _ in range(300):
+        w = rng.standard_normal(256).astype(np.float32)
+        codes, word, _ = ref.quantize_block(w)
+        ratio.append(np_f16(word) / ref.forward_block(w).std())
+        zeros.append(np.mean(codes == 1))
+    assert abs(np.mean(ratio) - 0.7979) < 2e-4
+    assert abs(np.mean(zeros) - erf(0.7979 / 2 / sqrt(2))) < 0.01
+
+
+# ------------------------------------------------------------------------------ format pins
+
+
+def test_layout_is_a_bijection_and_matches_second_decoder(ref):
+    N, K = 40, 768  # ragged: 2.5 row tiles
+    W = synth.weights(N, K, "layout")
+    codes, scales, flags = ref.quantize(W)
+    assert flags == 0
+    assert codes.size * 4 == 3 * 3 * 1536 and scales.size * 4 == 3 * 3 * 64
+    c, d, z = unpack_numpy(codes, scales, N, K)
+    for n in (0, 1, 15, 16, 39):
+        for b in range(3):
+            cb, word, _ = ref.quantize_block(W[n, 256 * b : 256 * b + 256])
+            assert np.array_equal(c[n, 256 * b : 256 * b + 256], cb)
+            assert d[n, b] == np_f16(word) and z[n, b] == np_f16(word >> 16)
+    # every code bit has its own position: flipping element (r, e) changes exactly one low-plane
+    # field; the high plane is all zero on encode; padding rows hold code 1 and scale 0
+    t = codes.reshape(3, 3, 384)
+    assert not t[:, :, 256:].any()
+    cpad, dpad, _ = unpack_numpy(codes, scales, 48, K)
+    assert np.all(cpad[40:] == 1) and not dpad[40:].any()
+    seen = set()
+    for r in range(16):
+        for e in range(256):
+            lane, i = 16 * (e >> 6) + r, e & 63
+            pos = (4 * lane + (i >> 4), 2 * (i & 15))
+            assert pos not in seen
+            seen.add(pos)
+    assert len(seen) == 4096 and max(p[0] for p in seen) == 255
+
+
+def test_dequantize_against_dense_definition(ref):
+    """Prop. 1: w_hat = H (d (q - z)), here with a dense normalised H in numpy."""
+    N, K = 24, 512
+    W = synth.weights(N, K, "deq")
+    W[:, 0] += 0.5  # provoke non-zero zero-points
+    codes, scales, _ = ref.quantize(W)
+    c, d, z = unpack_numpy(codes, scales, N, K)
+    assert (z != 0).any()
+    H = dense_hu().astype(np.float64) / 16.0
+    want = np.empty((N, K))
+    for b in range(K // 256):
+        v = d[:, b : b + 1] * ((c[:, 256 * b : 256 * b + 256] - 1) - z[:, b : b + 1])
+        want[:, 256 * b : 256 * b + 256] = v @ H.T
+    got = ref.dequantize(codes, scales, N, K)
+    assert np.allclose(got, want, rtol=0, atol=1e-15 * np.abs(want).max() * 256)
+    # App. B's listing describes the same computation for z = 0: smem = d (raw - 1), transform, x 0.0625
+    nz = z[:, 0] == 0
+    v = d[nz, 0:1] * (c[nz, :256] - 1)
+    assert np.allclose(got[nz, :256], (v @ dense_hu().astype(np.float64)) * 0.0625, rtol=0, atol=1e-14)
+
+
+def test_bad_code_is_flagged(ref):
+    codes, scales = synth.random_packed(16, 256, "bad")
+    _, flags = ref.dequantize(codes, scales, 16, 256, return_flags=True)
+    assert flags == 0
+    bad = codes.copy()
+    bad[5] |= 3 << 6  # low-plane field 3
+    assert ref.dequantize(bad, scales, 16, 256, return_flags=True)[1] & ref.FLAG_BAD_CODE
+    bad = codes.copy()
+    bad[256 + 9] |= 1 << 4  # a high-plane bit
+    assert ref.dequantize(bad, scales, 16, 256, return_flags=True)[1] & ref.FLAG_BAD_CODE
+
+
+# ------------------------------------------------------------------------------ error bound pins
+
+
+def test_error_identity_and_bounds(ref):
+    """Thm 2.  (i) isometry: ||w_hat - w|| = ||d(q - z) - w'||.  (ii) the printed bound
+    n d^2 / 4 holds for blocks whose coefficients all lie in the representable range; (iii) with
+    clipping the per-element error is max(d/2, |w'/d + z| - 1) d at most."""
+    rng = np.random.default_rng(11)
+    N, K = 32, 256
+    W = synth.weights(N, K, "bound")
+    codes, scales, _ = ref.quantize(W)
+    c, d, z = unpack_numpy(codes, scales, N, K)
+    What = ref.dequantize(codes, scales, N, K)
+    violations = 0
+    for n in range(N):
+        wt = ref.forward_block(W[n])
+        grid = d[n, 0] * ((c[n] - 1) - z[n, 0])
+        lhs = np.linalg.norm(What[n] - W[n].astype(np.float64))
+        assert abs(lhs - np.linalg.norm(grid - wt)) < 1e-12 * max(lhs, 1e-30)
+        u = wt / d[n, 0] + z[n, 0]
+        per_elem = np.maximum(0.5, np.abs(u) - 1.0) * d[n, 0]
+        assert np.all(np.abs(grid - wt) <= per_elem * (1 + 1e-12))
+        assert lhs**2 <= np.sum(per_elem**2) * (1 + 1e-12)
+        if np.all(np.abs(u) <= 1.5):
+            assert lhs**2 <= 256 * d[n, 0] ** 2 / 4 * (1 + 1e-12)
+        else:
+            violations += lhs**2 > 256 * d[n, 0] ** 2 / 4
+    # heavy-tailed blocks do clip: the unconditional form of the bound does not hold for them
+    assert violations > 0
+    # blocks constructed inside the representable range satisfy the printed bound
+    for _ in range(50):
+        q = rng.integers(-1, 2, size=256)
+        u = rng.uniform(-0.49, 0.49, size=256)
+        dd = 0.01
+        wt = dd * (q + u)
+        w = (ref.fwht256(wt) / 16.0).astype(np.float32)
+        cb, word, _ = ref.quantize_block(w)
+        dh, zh = np_f16(word), np_f16(word >> 16)
+        wt2 = ref.forward_block(w)
+        if np.all(np.abs(wt2 / dh + zh) <= 1.5):
+            err = np.linalg.norm(dh * ((cb.astype(np.float64) - 1) - zh) - wt2)
+            assert err**2 <= 256 * dh**2 / 4 * (1 + 1e-12)
+
+
+# ------------------------------------------------------------------------------ matmul pins
+
+
+def test_matmul_brute_force_tiny(ref):
+    """Dequantise with a dense H, multiply with a python double loop."""
+    N, K, M = 4, 512, 3
+    W = synth.weights(N, K, "tiny")
+    W[1, 256] = 0.7
+    X = synth.activations(M, K, "tiny")
+    codes, scales, _ = ref.quantize(W)
+    c, d, z = unpack_numpy(codes, scales, N, K)
+    H = dense_hu().astype(np.float64) / 16.0
+    What = np.concatenate([(H @ (d[:, b : b + 1] * ((c[:, 256 * b : 256 * b + 256] - 1) - z[:, b : b + 1])).T).T for b in range(2)], axis=1)
+    Y = ref.matmul(codes, scales, N, K, X)
+    for m in range(M):
+        for n in range(N):
+            acc = 0.0
+            for k in range(K):
+                acc += float(X[m, k]) * What[n, k]
+            assert abs(Y[m, n] - acc) <= 1e-13 * np.abs(What[n]).sum() * 10
+    # sub-range interface fills only the requested rows
+    Y2 = ref.matmul(codes, scales, N, K, X, rows=(1, 3))
+    assert np.array_equal(Y2[:, 1:3], Y[:, 1:3]) and not Y2[:, 0].any() and not Y2[:, 3].any()
+
+
+def test_rotation_can_move_to_the_activations(ref):
+    """<H v, x> = <v, H x>: contracting the un-rotated grid values with rotated activations gives
+    the same product (Sec. 2.3: H symmetric and its own inverse)."""
+    N, K, M = 16, 1024, 5
+    W = synth.weights(N, K, "side")
+    W[:, 512] += 0.4
+    X = synth.activations(M, K, "side")
+    codes, scales, _ = ref.quantize(W)
+    c, d, z = unpack_numpy(codes, scales, N, K)
+    Y = ref.matmul(codes, scales, N, K, X)
+    Xt = np.stack([np.concatenate([ref.fwht256(X[m, 256 * b : 256 * b + 256].astype(np.float64)) / 16.0 for b in range(K // 256)]) for m in range(M)])
+    grid = np.repeat(d, 256, axis=1) * ((c - 1) - np.repeat(z, 256, axis=1))
+    Y2 = Xt @ grid.T
+    assert np.allclose(Y, Y2, rtol=0, atol=1e-12 * np.abs(Y).max())
+    # and the zero-point term only needs the first activation of each block: sum_j (Hx)_j = 16 x_0
+    s = Xt.reshape(M, K // 256, 256).sum(axis=2)
+    assert np.allclose(s, 16.0 * X[:, ::256].astype(np.float64), rtol=0, atol=1e-11)
+
+
+def test_config5_block_count():
+    per_layer = sum(n * (k // 256) * copies for _, n, k, copies in synth.LLAMA70B_LAYER)
+    assert 80 * per_layer == 267_386_880  # 26.74 GB at 100 bytes per block
