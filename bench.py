@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the ITQ3_S hot path on one MI355X.
+
+A step is one decode pass (M = 1) over every weight tensor of a transformer-shaped stack: for each
+tensor one itq3s_matmul call (activation rotation + streaming contraction + epilogue) on packed
+weights that are resident in HBM.  The default workload is the Llama-7B-shaped configuration
+(32 layers x {4 x 4096x4096, 2 x 11008x4096, 1 x 4096x11008}, 2.5 GB packed, so that no tensor is
+re-read from a cache); `--workload llama70b_decode` runs the 80-layer 70B-shaped stream (26.7 GB).
+Weights are synthetic (Student-t, see paper_2603_27914_amd/synth.py), generated on the device and
+packed by itq3s_quantize, which is timed as well.
+
+Prints ONE JSON line.  `value` = packed-weight bytes streamed per second over the whole step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
+
+WORKLOADS = {
+    # name: (layers, [(tensor, N, K, copies)], M)
+    "llama7b_decode": (32, "LLAMA7B_LAYER", 1),
+    "llama70b_decode": (80, "LLAMA70B_LAYER", 1),
+}
+
+
+def student_t_weights(torch, gen, N, K):
+    """0.02 * Student-t(nu=4) on the device, round(0.001 K) input channels times 20."""
+    z = torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32)
+    chi = torch.zeros((N, K), device="cuda", dtype=torch.float32)
+    for _ in range(4):
+        chi += torch.randn((N, K), generator=gen, device="cuda", dtype=torch.float32) ** 2
+    W = z / torch.sqrt(chi / 4.0) * 0.02
+    ncol = int(round(0.001 * K))
+    cols = torch.randperm(K, generator=gen, device="cuda")[:ncol]
+    W[:, cols] *= 20.0
+    return W
+
+
+def activations(torch, gen, M, K):
+    X = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.float32)
+    cols = torch.randperm(K, generator=gen, device="cuda")[: int(round(0.005 * K))]
+    X[:, cols] *= 10.0
+    return X.to(torch.float16)
+
+
+def packed_bytes(N, K):
+    return ((N + 15) // 16) * (K // 256) * 1600
+
+
+def alg_bytes(N, K, M, y_bytes=4):
+    return packed_bytes(N, K) + M * K * 2 + M * N * y_bytes
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-shape, prefill and CPU-oracle legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2603_27914_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    binding.lib()
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.MASTER_SEED)
+
+    layers, layer_name, M = WORKLOADS[args.workload]
+    if args.layers > 0:
+        layers = args.layers
+    layer = getattr(synth, layer_name)
+
+    # ------------------------------------------------------------------ build the resident weights
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tensors = []  # (N, K, codes, scales, layer index, tensor index)
+    q_ms, q_bytes = 0.0, 0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_build = time.time()
+    for li in range(layers):
+        for ti, (name, N, K, copies) in enumerate(layer):
+            for c in range(copies):
+                W = student_t_weights(torch, gen, N, K)
+                codes, scales = binding.alloc_packed(N, K)
+                ev0.record()
+                binding.itq3s_quantize(W, codes, scales, status_flags=flags)
+                ev1.record()
+                ev1.synchronize()
+                q_ms += ev0.elapsed_time(ev1)
+                q_bytes += N * K * 4 + packed_bytes(N, K)
+                tensors.append((N, K, codes, scales, li, ti))
+                del W
+    assert int(flags.item()) == 0, "quantizer raised data flags on synthetic weights"
+    t_build = time.time() - t_build
+    xs = {}
+    for name, N, K, copies in layer:
+        if K not in xs:
+            xs[K] = activations(torch, gen, M, K)
+    ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for _, N, K, _ in layer}
+    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for _, N, K, _ in layer), dtype=torch.uint8, device="cuda")
+
+    def step():
+        for N, K, codes, scales, li, ti in tensors:
+            binding.itq3s_matmul(codes, scales, N, K, xs[K], out=ys[N], workspace=ws, status_flags=None)
+
+    # ------------------------------------------------------------------ timed region
+    # The step is captured once into a HIP graph and replayed, so that the timed region measures
+    # the GPU and not the Python interpreter issuing several hundred launches.
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall_ms / args.steps
+    step_packed = sum(packed_bytes(N, K) for N, K, *_ in tensors)
+    step_alg = sum(alg_bytes(N, K, M) for N, K, *_ in tensors)
+    value = step_packed / (ms_per_step * 1e-3) / 1e9
+    calls = len(tensors)
+    # dominant kernel = the streaming contraction, one launch per call; average duration from the
+    # HIP events that bracket the timed region on the launch stream
+    avg_launch_ms = ev_ms / (args.steps * calls)
+    achieved = (step_alg / calls) / (avg_launch_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "ITQ3_S GEMV effective HBM GB/s on packed-weight bytes @M=1",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: %d layers x %s, M=%d, %d matmul calls, %.2f GB packed resident in HBM"
+            % (args.workload, layers, "+".join("%dx(%dx%d)" % (c, N, K) for _, N, K, c in layer), M, calls, step_packed / 1e9),
+            "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "gemv_kernel (itq3s_matmul, M<=16 path)",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "avg_launch_us": round(avg_launch_ms * 1e3, 3),
+            "alg_bytes_per_launch": int(step_alg / calls),
+        },
+        "quantize": {"GBps": round(q_bytes / (q_ms * 1e-3) / 1e9, 1), "bytes": q_bytes, "ms": round(q_ms, 2), "frac_of_hbm_peak": round(q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+    }
+
+    if not args.no_extras:
+        out["per_shape"] = per_shape_leg(torch, binding, tensors, layer, gen)
+        out["prefill"] = prefill_leg(torch, binding, synth, gen)
+        out["dequantize"] = dequantize_leg(torch, binding, tensors)
+        out["cpu_baseline"] = cpu_baseline_leg(torch, binding, tensors, layer, xs, M)
+    print(json.dumps(out))
+
+
+def time_calls(torch, fn, n_iter, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n_iter):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / n_iter
+
+
+def per_shape_leg(torch, binding, tensors, layer, gen):
+    """Each shape on its own, cycling through all resident copies of that shape (so the weights
+    come from HBM, not from a cache), for M = 1 and a batched M."""
+    res = []
+    for ti, (name, N, K, copies) in enumerate(layer):
+        same = [t for t in tensors if t[5] == ti]
+        for M in (1, 8):
+            X = activations(torch, gen, M, K)
+            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+
+            def run():
+                for N_, K_, codes, scales, *_ in same:
+                    binding.itq3s_matmul(codes, scales, N_, K_, X, out=Y, workspace=ws)
+
+            ms = time_calls(torch, run, 5) / len(same)
+            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 2), "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1), "copies": len(same)})
+    return res
+
+
+def prefill_leg(torch, binding, synth, gen):
+    """The MFMA path: X fp16 [M, K] times the two FFN-shaped tensors, M = 512 and 2048."""
+    res = []
+    for name, N, K in synth.SHAPES["prefill"]:
+        W = student_t_weights(torch, gen, N, K)
+        codes, scales = binding.itq3s_quantize(W)
+        del W
+        for M in (512, 2048):
+            X = activations(torch, gen, M, K)
+            Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+            ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+            ms = time_calls(torch, lambda: binding.itq3s_matmul(codes, scales, N, K, X, out=Y, workspace=ws), 20)
+            tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 1), "TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)})
+    return res
+
+
+def dequantize_leg(torch, binding, tensors):
+    N, K, codes, scales, *_ = max(tensors, key=lambda t: t[0] * t[1])
+    out = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    ms = time_calls(torch, lambda: binding.itq3s_dequantize(codes, scales, N, K, out=out), 10)
+    nbytes = packed_bytes(N, K) + N * K * 4
+    return {"N": N, "K": K, "us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+
+
+def cpu_baseline_leg(torch, binding, tensors, layer, xs, M):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the M = 1 matmuls of
+    the first layers' tensors, single thread.  Also checks the GPU result of those calls against it."""
+    from oracle import itq3s_ref as ref
+
+    ref.build()
+    n_layers = 5 if len(layer) <= 3 else 1  # about 10-20 s of single-thread work
+    sample = [t for t in tensors if t[4] < n_layers]
+    secs, nbytes, worst = 0.0, 0, 0.0
+    for N, K, codes, scales, li, ti in sample:
+        hc, hs = codes.cpu().numpy().view(np.uint32), scales.cpu().numpy().view(np.uint32)
+        X = xs[K].cpu().numpy()
+        t0 = time.perf_counter()
+        Yr = ref.matmul(hc, hs, N, K, X)
+        secs += time.perf_counter() - t0
+        nbytes += packed_bytes(N, K)
+        Y = binding.itq3s_matmul(codes, scales, N, K, xs[K]).cpu().numpy()
+        worst = max(worst, float(np.max(np.linalg.norm(Y - Yr, axis=1) / np.linalg.norm(Yr, axis=1))))
+    return {
+        "value": round(nbytes / secs / 1e9, 4),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "M=%d matmul of every tensor of the first %d layer(s) (%d tensors, %.1f MB packed), %.1f s of CPU time" % (M, n_layers, len(sample), nbytes / 1e6, secs),
+        "gpu_vs_oracle_max_rel_l2": worst,
+    }
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,111 @@
+/*
+ * libitq3s -- ITQ3_S fused 3-bit ternary matmul for AMD MI355X (gfx950).  C ABI.
+ *
+ * ITQ3_S (arxiv 2603.27914) stores a weight matrix W[N,K] in blocks of 256 consecutive input
+ * channels of one output row.  Each block is rotated by the normalised 256-point Walsh-Hadamard
+ * transform H, scaled, and coded with ternary digits; 256 three-bit codes + fp16 scale d + fp16
+ * zero-point z = 100 bytes (Sec. 4.1).  Reconstruction is w_hat = H( d (q - z) ) (Prop. 1).
+ *
+ * Conventions for every call below
+ *   - all data pointers are DEVICE pointers owned by the caller; the library never allocates,
+ *     frees or synchronises.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL =
+ *     the default stream) and the call returns at once.
+ *   - the return value is 0 (ITQ3S_OK) or a negative ITQ3S_ERR_* code.  Argument errors are found
+ *     on the host before anything is launched; then no kernel runs and no memory is touched.
+ *   - `status_flags` (may be NULL) is one device uint32 into which kernels OR data-condition bits
+ *     (ITQ3S_FLAG_*); the caller clears and reads it.
+ *   - K must be a multiple of 256 (the paper leaves other widths open, Sec. 8).  N is arbitrary;
+ *     storage is padded to a multiple of 16 rows.
+ *
+ * Packed layout (Sec. 4.1-4.2; the paper's word formula is not self-consistent, the bit positions
+ * are this library's choice within the 96 + 2 + 2 byte budget):
+ *   KB = K/256, NT = ceil(N/16).  Tile (nt, b) = rows 16nt..16nt+15 x channels 256b..256b+255,
+ *   stored at index nt*KB + b.
+ *   codes : NT*KB tiles of 384 little-endian uint32 (1536 bytes = 16 blocks x 96 bytes).
+ *           For element e (0..255) of tile row r (0..15), code c = q+1 in {0,1,2}:
+ *             lane = 16*(e>>6) + r,  i = e & 63
+ *             low plane  word 4*lane + (i>>4),       bits [2(i&15)+1 : 2(i&15)] = c & 3
+ *             high plane word 256 + 2*lane + (i>>5), bit  (i&31)                = c >> 2  (0 on encode)
+ *           i.e. wavefront lane `lane` finds its 64 codes in one 16-byte and one 8-byte load, laid
+ *           out as the 16x16xK MFMA operand of row r.
+ *   scales: NT*KB*16 uint32; word (nt*KB + b)*16 + r = fp16 bits of d | fp16 bits of z << 16.
+ *   Rows >= N of the last tile hold code 1 and scale word 0.
+ */
+#ifndef ITQ3S_H
+#define ITQ3S_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ITQ3S_OK 0
+#define ITQ3S_ERR_NULL (-1)      /* a required pointer is NULL                                    */
+#define ITQ3S_ERR_SHAPE (-2)     /* N, K, M <= 0, K % 256 != 0, or a leading dimension too small   */
+#define ITQ3S_ERR_ALIGN (-3)     /* a pointer or leading dimension breaks the stated alignment     */
+#define ITQ3S_ERR_DTYPE (-4)     /* dtype argument is not ITQ3S_F32 / ITQ3S_F16                    */
+#define ITQ3S_ERR_WORKSPACE (-5) /* workspace NULL or smaller than itq3s_matmul_workspace_bytes    */
+#define ITQ3S_ERR_LAUNCH (-6)    /* the HIP runtime refused a launch (see hipGetLastError)         */
+
+#define ITQ3S_F32 0
+#define ITQ3S_F16 1
+
+#define ITQ3S_FLAG_NONFINITE 1u /* quantize: a weight was NaN/Inf; its block is stored as zeros    */
+#define ITQ3S_FLAG_SCALE_SAT 2u /* quantize: d exceeded the fp16 range and was clamped to 65504    */
+#define ITQ3S_FLAG_Z_CLAMP 4u   /* quantize: |z| exceeded 2048 and was clamped                     */
+#define ITQ3S_FLAG_BAD_CODE 8u  /* decode: a code outside {0,1,2} was met (dequantize checks both
+                                   planes; matmul checks the high plane only and treats a low-plane
+                                   3 as digit +2)                                                  */
+
+/* Sizes of the two packed arrays for W[N,K]: NT*KB*1536 and NT*KB*64 bytes (0 if K % 256 != 0). */
+size_t itq3s_codes_bytes(int64_t N, int64_t K);
+size_t itq3s_scales_bytes(int64_t N, int64_t K);
+
+/* Bytes of scratch itq3s_matmul needs for the rotated activations (Sec. 2.3: H is symmetric and
+ * its own inverse, so <H v, x> = <v, H x>; the library rotates X once per call instead of every
+ * weight block).  Never 0; grows with M*K. */
+size_t itq3s_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/* Offline quantization (Alg. 1, Def. 1).  Per block: w' = H w in fp64 (butterfly stages
+ * 1,2,4,...,128, then x 1/16); d = 0.7979 * population-std(w') rounded to fp16 through fp32;
+ * z = -floor(mean(w')/d + 0.5); code = 1 + clamp(floor(w'/d + z + 0.5), -1, 1), decided exactly
+ * through the thresholds (+-0.5 - z) d.  Sums are pairwise (neighbours first).  Results are
+ * bit-identical on any IEEE-754 machine.
+ *   W      [in]  device, N x K fp32 row-major, row stride ldw elements (ldw >= K, ldw % 4 == 0,
+ *                pointer 16-byte aligned)
+ *   codes  [out] device, itq3s_codes_bytes(N,K), 16-byte aligned
+ *   scales [out] device, itq3s_scales_bytes(N,K), 16-byte aligned */
+int itq3s_quantize(const float *W, int64_t N, int64_t K, int64_t ldw, uint32_t *codes, uint32_t *scales,
+                   uint32_t *status_flags, void *stream);
+
+/* Weight-side reconstruction (Alg. 2, Prop. 1): W_out[n][k] = ( H( d (q - z) ) )[k], computed with
+ * exact integer butterflies and one rounding to the output type.
+ *   W_out [out] device, N x K of out_dtype (ITQ3S_F32 or ITQ3S_F16), row stride ldo elements
+ *               (ldo >= K, ldo % 4 == 0, pointer 16-byte aligned) */
+int itq3s_dequantize(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, void *W_out, int out_dtype,
+                     int64_t ldo, uint32_t *status_flags, void *stream);
+
+/* Fused matmul (problem statement of Alg. 2; Sec. 5.4 for M = 1):  Y[m][n] = sum_k X[m][k] w_hat[n][k].
+ * No dequantized weight is written to memory.  M <= 16 takes the bandwidth-bound streaming path,
+ * larger M the tiled MFMA path; fp32 accumulation in both.
+ *   X  [in]  device, M x K fp16 row-major, row stride ldx elements (ldx >= K, ldx % 8 == 0,
+ *            pointer 16-byte aligned)
+ *   Y  [out] device, M x N of y_dtype, row stride ldy elements (ldy >= N); overwritten
+ *   workspace [scratch] device, 256-byte aligned, at least itq3s_matmul_workspace_bytes(M,N,K);
+ *            contents undefined afterwards; calls sharing a workspace must be stream-ordered */
+int itq3s_matmul(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M, int64_t ldx,
+                 void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
+                 void *stream);
+
+/* Static text for a status code.  Never NULL. */
+const char *itq3s_strerror(int status);
+
+/* major*10000 + minor*100 + patch */
+int itq3s_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ITQ3S_H */

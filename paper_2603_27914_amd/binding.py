@@ -1,0 +1,152 @@
+"""Thin ctypes binding over libitq3s (the C ABI declared in include/itq3s.h).
+
+Argument marshalling only: torch tensors supply device memory and the current HIP stream; every
+step of the computation runs in the library's kernels.  There is no CPU fallback -- if the shared
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libitq3s.so")
+
+F32, F16 = 0, 1
+FLAG_NONFINITE, FLAG_SCALE_SAT, FLAG_Z_CLAMP, FLAG_BAD_CODE = 1, 2, 4, 8
+
+EXPORTS = [
+    "itq3s_codes_bytes",
+    "itq3s_scales_bytes",
+    "itq3s_matmul_workspace_bytes",
+    "itq3s_quantize",
+    "itq3s_dequantize",
+    "itq3s_matmul",
+    "itq3s_strerror",
+    "itq3s_version",
+]
+
+_lib = None
+
+
+class Itq3sError(RuntimeError):
+    pass
+
+
+def lib():
+    """Load libitq3s.so (built by ``paper_2603_27914_amd.build`` / ``__graft_entry__.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise Itq3sError("libitq3s.so is not built: run `python -m paper_2603_27914_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.itq3s_codes_bytes.restype = sz
+        L.itq3s_codes_bytes.argtypes = [i64, i64]
+        L.itq3s_scales_bytes.restype = sz
+        L.itq3s_scales_bytes.argtypes = [i64, i64]
+        L.itq3s_matmul_workspace_bytes.restype = sz
+        L.itq3s_matmul_workspace_bytes.argtypes = [i64, i64, i64]
+        L.itq3s_quantize.restype = ci
+        L.itq3s_quantize.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+        L.itq3s_dequantize.restype = ci
+        L.itq3s_dequantize.argtypes = [vp, vp, i64, i64, vp, ci, i64, vp, vp]
+        L.itq3s_matmul.restype = ci
+        L.itq3s_matmul.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
+        L.itq3s_strerror.restype = ctypes.c_char_p
+        L.itq3s_strerror.argtypes = [ci]
+        L.itq3s_version.restype = ci
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise Itq3sError("libitq3s: %s (status %d)" % (lib().itq3s_strerror(status).decode(), status))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _need_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise Itq3sError("libitq3s works on device memory only; got a CPU tensor")
+
+
+def itq3s_codes_bytes(N, K):
+    return lib().itq3s_codes_bytes(N, K)
+
+
+def itq3s_scales_bytes(N, K):
+    return lib().itq3s_scales_bytes(N, K)
+
+
+def itq3s_matmul_workspace_bytes(M, N, K):
+    return lib().itq3s_matmul_workspace_bytes(M, N, K)
+
+
+def itq3s_version():
+    return lib().itq3s_version()
+
+
+def alloc_packed(N, K, device="cuda"):
+    """Uninitialised (codes int32[...], scales int32[...]) tensors of the right size."""
+    cb, sb = itq3s_codes_bytes(N, K), itq3s_scales_bytes(N, K)
+    if cb == 0:
+        raise Itq3sError("bad shape: K must be a positive multiple of 256")
+    return torch.empty(cb // 4, dtype=torch.int32, device=device), torch.empty(sb // 4, dtype=torch.int32, device=device)
+
+
+def itq3s_quantize(W, codes=None, scales=None, status_flags=None):
+    """W: float32 [N, K] device tensor (row stride arbitrary) -> (codes, scales) int32 device tensors."""
+    _need_cuda(W, codes, scales, status_flags)
+    if W.dtype != torch.float32 or W.dim() != 2 or W.stride(1) != 1:
+        raise Itq3sError("W must be float32 [N, K] with unit column stride")
+    N, K = W.shape
+    if codes is None or scales is None:
+        codes, scales = alloc_packed(N, K, W.device)
+    _check(lib().itq3s_quantize(_ptr(W), N, K, W.stride(0), _ptr(codes), _ptr(scales), _ptr(status_flags), _stream()))
+    return codes, scales
+
+
+def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_flags=None):
+    """-> reconstructed weights [N, K] (float32 or float16) on the device."""
+    _need_cuda(codes, scales, out, status_flags)
+    if out is None:
+        out = torch.empty((N, K), dtype=dtype, device=codes.device)
+    if out.dtype not in (torch.float32, torch.float16) or out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (N, K):
+        raise Itq3sError("out must be float32/float16 [N, K] with unit column stride")
+    _check(
+        lib().itq3s_dequantize(
+            _ptr(codes), _ptr(scales), N, K, _ptr(out), F16 if out.dtype == torch.float16 else F32, out.stride(0), _ptr(status_flags), _stream()
+        )
+    )
+    return out
+
+
+def itq3s_matmul(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None):
+    """Y[M, N] = X[M, K] @ W_hat[N, K]^T from the packed weights.  X: float16 device tensor."""
+    _need_cuda(codes, scales, X, out, workspace, status_flags)
+    if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
+        raise Itq3sError("X must be float16 [M, K] with unit column stride")
+    M = X.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=X.device)
+    if out.dtype not in (torch.float32, torch.float16) or out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (M, N):
+        raise Itq3sError("out must be float32/float16 [M, N] with unit column stride")
+    need = itq3s_matmul_workspace_bytes(M, N, K)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    _check(
+        lib().itq3s_matmul(
+            _ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
+            out.stride(0), _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(status_flags), _stream(),
+        )
+    )
+    return out

@@ -1,0 +1,114 @@
+// C-ABI entry points of libitq3s: argument validation on the host, then launches.  See
+// include/itq3s.h for the contract of every call.
+#include "../../include/itq3s.h"
+#include "itq3s_kernels.h"
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline int pad_m(int64_t M) {
+    int mp = 1;
+    while (mp < M) mp <<= 1;
+    return mp;
+}
+
+struct WorkspacePlan {
+    size_t xt_bytes, s_bytes, total;
+};
+
+WorkspacePlan plan_workspace(int64_t M, int64_t K) {
+    WorkspacePlan p;
+    const int64_t rows = M <= itq3s::kGemvMaxM ? pad_m(M) : M;
+    p.xt_bytes = round_up((size_t)rows * (size_t)K * 2, 256);
+    p.s_bytes = M <= itq3s::kGemvMaxM ? round_up((size_t)rows * (size_t)(K / 256) * 4, 256) : 0;
+    p.total = p.xt_bytes + p.s_bytes + 256;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t itq3s_codes_bytes(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0 || K % 256 != 0) return 0;
+    return (size_t)((N + 15) / 16) * (size_t)(K / 256) * 1536u;
+}
+
+size_t itq3s_scales_bytes(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0 || K % 256 != 0) return 0;
+    return (size_t)((N + 15) / 16) * (size_t)(K / 256) * 64u;
+}
+
+size_t itq3s_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    (void)N;
+    if (M <= 0 || K <= 0 || K % 256 != 0) return 256;
+    return plan_workspace(M, K).total;
+}
+
+int itq3s_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* status_flags,
+                   void* stream) {
+    if (!W || !codes || !scales) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || K % 256 != 0 || ldw < K) return ITQ3S_ERR_SHAPE;
+    if (((N + 15) / 16) * (K / 256) > 0x7fffffffLL) return ITQ3S_ERR_SHAPE;
+    if (!aligned(W, 16) || ldw % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    return itq3s::launch_quantize(W, N, K, ldw, codes, scales, status_flags, static_cast<hipStream_t>(stream));
+}
+
+int itq3s_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* W_out, int out_dtype, int64_t ldo,
+                     uint32_t* status_flags, void* stream) {
+    if (!codes || !scales || !W_out) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || K % 256 != 0 || ldo < K) return ITQ3S_ERR_SHAPE;
+    if (((N + 15) / 16) * (K / 256) > 0x7fffffffLL) return ITQ3S_ERR_SHAPE;
+    if (out_dtype != ITQ3S_F32 && out_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
+    if (!aligned(W_out, 16) || ldo % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    return itq3s::launch_dequantize(codes, scales, N, K, W_out, out_dtype == ITQ3S_F16, ldo, status_flags, static_cast<hipStream_t>(stream));
+}
+
+int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx, void* Y,
+                 int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream) {
+    if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
+    if ((N + 15) / 16 > 0x7fffffffLL / (K / 256) || M > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
+    if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
+    if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) ||
+        (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    if (!workspace || workspace_bytes < itq3s_matmul_workspace_bytes(M, N, K)) return ITQ3S_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return ITQ3S_ERR_ALIGN;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const WorkspacePlan p = plan_workspace(M, K);
+    _Float16* Xt = static_cast<_Float16*>(workspace);
+    const _Float16* Xh = static_cast<const _Float16*>(X);
+    if (M <= itq3s::kGemvMaxM) {
+        const int MP = pad_m(M);
+        float* S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.xt_bytes);
+        int rc = itq3s::launch_rotate_frag(Xh, M, K, ldx, MP, Xt, S, st);
+        if (rc != 0) return rc;
+        return itq3s::launch_gemv(codes, scales, N, K, Xt, S, M, MP, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+    }
+    int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, st);
+    if (rc != 0) return rc;
+    return itq3s::launch_gemm(codes, scales, N, K, Xt, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+}
+
+const char* itq3s_strerror(int status) {
+    switch (status) {
+        case ITQ3S_OK: return "ok";
+        case ITQ3S_ERR_NULL: return "a required pointer is NULL";
+        case ITQ3S_ERR_SHAPE: return "bad shape: sizes must be positive, K a multiple of 256, leading dimensions large enough";
+        case ITQ3S_ERR_ALIGN: return "pointer or leading dimension not aligned as required";
+        case ITQ3S_ERR_DTYPE: return "dtype must be ITQ3S_F32 or ITQ3S_F16";
+        case ITQ3S_ERR_WORKSPACE: return "workspace missing or smaller than itq3s_matmul_workspace_bytes()";
+        case ITQ3S_ERR_LAUNCH: return "HIP refused the kernel launch";
+    }
+    return "unknown status";
+}
+
+int itq3s_version(void) { return 100; }
+
+}  // extern "C"

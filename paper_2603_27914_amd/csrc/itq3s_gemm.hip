@@ -1,0 +1,162 @@
+// Tiled matmul for M > 16 activation rows (the prefill path): a dense contraction on the matrix
+// cores.  Alg. 2 dequantizes a weight tile into on-chip memory and multiplies from there; here the
+// tile written to LDS holds the un-rotated grid values d (q - z) in fp16 (exact for z = 0), the
+// rotation having been moved to the activations (Sec. 2.3: <H v, x> = <v, H x>), so the tile loader
+// needs two packed-fp16 operations per pair of weights and no butterflies.
+//
+//   Y[m][n] = sum_k x~[m][k'] * g[n][k'],   g = d (c - 1 - z)
+//
+// k' is the channel order the unpack produces (within each group of 16 channels: 0,8,1,9,...,7,15);
+// the rotation kernel writes x~ in the same order, so both LDS tiles are plain [row][k'].
+//
+// Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 (m) x 128 (n) x 64 (k), wavefront tile 64 x 64
+// as 2 x 2 v_mfma_f32_32x32x16_f16.  A operand = x~ rows, B operand = weight rows, so a lane's
+// accumulator column is an output channel n and stores are contiguous along n.
+#include "itq3s_dev.h"
+#include "itq3s_kernels.h"
+
+namespace itq3s {
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDT = BK + 8;  // LDS row stride in halves (padding keeps 16-byte reads conflict-free)
+
+struct GemmArgs {
+    const uint32_t* codes;
+    const uint32_t* scales;
+    const _Float16* Xt;  // [M][K] in k' order
+    void* Y;
+    uint32_t* flags;
+    int64_t N, K, M, ldy;
+    int NT, KB, y_f16;
+};
+
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
+    __shared__ __align__(16) _Float16 As[BM * LDT];
+    __shared__ __align__(16) _Float16 Bs[BN * LDT];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;  // wavefront position in the 2 x 2 arrangement
+    const int64_t m0 = (int64_t)blockIdx.y * BM;
+    const int nt0 = blockIdx.x * (BN / 16);
+    const int KT = (int)(a.K / BK);
+
+    // weight loader role: 16-row tile tl, row r, half p of the 64-channel quarter
+    const int wp = tid & 1, wr = (tid >> 1) & 15, wtl = tid >> 5;
+    const bool w_ok = nt0 + wtl < a.NT;
+    // activation loader role: four 16-byte pieces per thread
+    uint4 xa[4];
+    uint2 wlo;
+    uint32_t whi = 0, wsc = 0, bad = 0;
+
+    auto load_global = [&](int kt) {
+        const int b = kt >> 2, q = kt & 3;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i, row = idx >> 3, c16 = idx & 7;
+            const int64_t m = m0 + row;
+            xa[i] = m < a.M ? *reinterpret_cast<const uint4*>(a.Xt + m * a.K + (int64_t)kt * BK + c16 * 8) : make_uint4(0, 0, 0, 0);
+        }
+        if (w_ok) {
+            const int64_t tile = (int64_t)(nt0 + wtl) * a.KB + b;
+            const uint32_t* t = a.codes + tile * kTileWords;
+            const int ln = 16 * q + wr;
+            wlo = *reinterpret_cast<const uint2*>(t + 4 * ln + 2 * wp);
+            whi = t[kTileLoWords + 2 * ln + wp];
+            wsc = a.scales[tile * kTileRows + wr];
+        } else {
+            wlo = make_uint2(0x55555555u, 0x55555555u);
+            whi = 0;
+            wsc = 0;
+        }
+    };
+
+    auto store_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i, row = idx >> 3, c16 = idx & 7;
+            *reinterpret_cast<uint4*>(&As[row * LDT + c16 * 8]) = xa[i];
+        }
+        bad |= whi;
+        // g = d * (c - 1 - z): c * 2^-14 sits in bits 11:10 of each half after shift-and-mask
+        const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(wsc & 0xffffu));
+        const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(wsc >> 16));
+        const half2v dd = {d, d};
+        const half2v k14 = {(_Float16)16384.0f, (_Float16)16384.0f};
+        const _Float16 off1 = (_Float16)(-1.0f) - z;
+        const half2v off = {off1, off1};
+        const uint32_t w2[2] = {wlo.x, wlo.y};
+        _Float16* dst = &Bs[(wtl * 16 + wr) * LDT + 32 * wp];
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            uint32_t o[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int sh = 10 - 2 * j;
+                const uint32_t bits = (sh >= 0 ? (w2[w] << sh) : (w2[w] >> (-sh))) & 0x0C000C00u;
+                half2v h = __builtin_bit_cast(half2v, bits);
+                h = (h * k14 + off) * dd;
+                o[j] = __builtin_bit_cast(uint32_t, h);
+            }
+            *reinterpret_cast<uint4*>(dst + 16 * w) = make_uint4(o[0], o[1], o[2], o[3]);
+            *reinterpret_cast<uint4*>(dst + 16 * w + 8) = make_uint4(o[4], o[5], o[6], o[7]);
+        }
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int l32 = lane & 31, kg = lane >> 5;
+    load_global(0);
+    for (int kt = 0; kt < KT; ++kt) {
+        __syncthreads();
+        store_lds();
+        __syncthreads();
+        if (kt + 1 < KT) load_global(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            half8 af[2], bf[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const half8*>(&As[(wm * 64 + i * 32 + l32) * LDT + ks * 16 + kg * 8]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const half8*>(&Bs[(wn * 64 + j * 32 + l32) * LDT + ks * 16 + kg * 8]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // accumulator register v of a 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = (int64_t)nt0 * 16 + wn * 64 + j * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                if (m < a.M && n < a.N) {
+                    if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[i][j][v];
+                    else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[i][j][v];
+                }
+            }
+        }
+    if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
+}
+
+int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
+                int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
+    GemmArgs a;
+    a.codes = codes; a.scales = scales; a.Xt = Xt; a.Y = Y; a.flags = flags;
+    a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
+    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
+    hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, a);
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+}  // namespace itq3s

@@ -1,0 +1,34 @@
+// Internal launch interface between the C-ABI entry points and the kernels.  Every launcher
+// assumes arguments were validated by the caller, enqueues on `stream` and returns 0 or -6.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace itq3s {
+
+constexpr uint32_t kFlagNonFinite = 1u, kFlagScaleSat = 2u, kFlagZClamp = 4u, kFlagBadCode = 8u;
+
+// Streaming path handles up to this many activation rows; more rows go to the tiled MFMA path.
+constexpr int kGemvMaxM = 16;
+
+int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* flags,
+                    hipStream_t stream);
+
+int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* out, int out_f16, int64_t ldo,
+                      uint32_t* flags, hipStream_t stream);
+
+// Rotated activations for the streaming path: Xt in MFMA operand order with MP (power of two >= M,
+// <= 16) columns, S[b*MP + m] = sum over the rounded rotated chunk.
+int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, hipStream_t stream);
+
+// Rotated activations for the tiled path: Xt[m][k] row-major, row stride K.
+int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, hipStream_t stream);
+
+int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const float* S, int64_t M,
+                int MP, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+
+int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
+                int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+
+}  // namespace itq3s

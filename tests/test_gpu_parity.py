@@ -1,0 +1,338 @@
+"""HIP path vs CPU oracle, through the C ABI (ctypes binding).  Needs a real MI355X: -m gpu.
+
+Bars: packed codes and scale words bit-exact; dequantize <= 1e-6 relative L2 per row (fp32 out);
+matmul <= 2e-3 relative L2 per activation row against the oracle's fp64 result computed from the
+same packed bytes."""
+import numpy as np
+import pytest
+
+from paper_2603_27914_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MATMUL_TOL = 2e-3
+DEQ_TOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_27914_amd import binding
+
+    binding.lib()  # fails loudly if the HIP library is not built
+    return torch, binding
+
+
+def to_dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def rel_rows(got, want):
+    num = np.linalg.norm(got.astype(np.float64) - want, axis=1)
+    den = np.linalg.norm(want, axis=1)
+    return np.max(num / np.maximum(den, 1e-300))
+
+
+# ----------------------------------------------------------------------------------- quantize
+
+
+def check_quantize(torch, binding, ref, W, ldw=None):
+    N, K = W.shape
+    if ldw is None:
+        Wd = to_dev(torch, W)
+    else:
+        buf = torch.zeros((N, ldw), dtype=torch.float32, device="cuda")
+        buf[:, :K] = to_dev(torch, W)
+        Wd = buf[:, :K]
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    codes, scales = binding.itq3s_quantize(Wd, status_flags=flags)
+    torch.cuda.synchronize()
+    rc, rs, rflags = ref.quantize(W)
+    assert np.array_equal(u32(scales), rs), "scale words differ"
+    assert np.array_equal(u32(codes), rc), "packed codes differ"
+    assert int(flags.item()) == rflags
+    return codes, scales
+
+
+def test_quantize_config1_bit_exact(gpu, ref):
+    torch, binding = gpu
+    W = synth.weights(2048, 2048, "single", n_outlier_cols=4)
+    check_quantize(torch, binding, ref, W)
+
+
+@pytest.mark.parametrize("N,K,ldw", [(1, 256, None), (40, 768, None), (17, 512, 520), (333, 1024, None)])
+def test_quantize_ragged_shapes(gpu, ref, N, K, ldw):
+    torch, binding = gpu
+    check_quantize(torch, binding, ref, synth.weights(N, K, "ragged", n_outlier_cols=2), ldw)
+
+
+def test_quantize_adversarial_blocks(gpu, ref):
+    torch, binding = gpu
+    rng = np.random.default_rng(42)
+    rows = []
+    rows.append(np.zeros(256, np.float32))  # all zero
+    rows.append(np.full(256, 0.37, np.float32))  # constant
+    e0 = np.zeros(256, np.float32); e0[0] = 3.0; rows.append(e0)  # spike at 0: sigma = 0
+    e5 = np.zeros(256, np.float32); e5[5] = -7.0; rows.append(e5)  # spike elsewhere
+    rows.append((rng.standard_normal(256) * 1e6).astype(np.float32))  # scale saturates
+    rows.append((rng.standard_normal(256) * 1e-7).astype(np.float32))  # subnormal fp16 scale
+    rows.append((rng.standard_normal(256) * 1e-9).astype(np.float32))  # scale underflows to 0
+    w = (rng.standard_normal(256) * 1e-3).astype(np.float32); w[0] = 1e3; rows.append(w)  # z clamps
+    w = (0.02 * rng.standard_t(4, 256)).astype(np.float32); w[0] = 0.9; rows.append(w)  # z != 0
+    w = (0.02 * rng.standard_t(4, 256)).astype(np.float32); w[0] = -1.7; rows.append(w)  # z != 0, other sign
+    w = rng.standard_normal(256).astype(np.float32); w[17] = np.inf; rows.append(w)
+    w = rng.standard_normal(256).astype(np.float32); w[200] = np.nan; rows.append(w)
+    rows.append(np.full(256, np.finfo(np.float32).max, np.float32) * np.sign(rng.standard_normal(256)).astype(np.float32))
+    rows.append((rng.standard_normal(256) * np.finfo(np.float32).tiny).astype(np.float32))  # fp32 subnormal range
+    # integer-valued transform-domain data: coefficients land exactly on decision thresholds
+    for _ in range(20):
+        target = rng.integers(-40, 41, size=256).astype(np.float64) * 16.0
+        rows.append((ref.fwht256(target) / 256.0).astype(np.float32))
+    W = np.stack(rows)
+    for K in (256,):
+        check_quantize(torch, binding, ref, W)
+    # the same blocks side by side in one row-major matrix with three block columns
+    W3 = np.concatenate([W, W[::-1], np.roll(W, 3, axis=0)], axis=1)
+    check_quantize(torch, binding, ref, W3)
+
+
+def test_quantize_many_random_blocks(gpu, ref):
+    """Half a million heavy-tailed blocks: any disagreement in rounding (sqrt, division, the two
+    conversion steps of the scale, the summation order) would flip a scale bit or a code somewhere."""
+    torch, binding = gpu
+    W = synth.weights(4096, 4096 * 8, "many", n_outlier_cols=33)
+    check_quantize(torch, binding, ref, W)
+
+
+# ----------------------------------------------------------------------------------- dequantize
+
+
+@pytest.mark.parametrize("N,K", [(16, 256), (40, 768), (2048, 2048)])
+def test_dequantize_fp32(gpu, ref, N, K):
+    torch, binding = gpu
+    W = synth.weights(N, K, "deq", n_outlier_cols=4)
+    W[:, 0] += 0.5  # non-zero zero-points in the first block column
+    codes, scales, _ = ref.quantize(W)
+    want = ref.dequantize(codes, scales, N, K)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = binding.itq3s_dequantize(to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32)), N, K, status_flags=flags)
+    got = got.cpu().numpy()
+    assert int(flags.item()) == 0
+    assert rel_rows(got, want) <= DEQ_TOL
+    # element-wise: one fp32 rounding of an exactly known product
+    assert np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-30)) <= 2.0**-23
+
+
+def test_dequantize_fp16_and_strided(gpu, ref):
+    torch, binding = gpu
+    N, K = 100, 512
+    codes, scales = synth.random_packed(N, K, "deq16", z_fraction=0.05)
+    want = ref.dequantize(codes, scales, N, K)
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    buf = torch.zeros((N, K + 8), dtype=torch.float16, device="cuda")
+    binding.itq3s_dequantize(cd, sd, N, K, out=buf[:, :K])
+    got = buf.cpu().numpy()
+    assert not got[:, K:].any()
+    # fp16 output: within one fp16 rounding of the exact value (the kernel rounds through fp32)
+    w16 = want.astype(np.float16).astype(np.float64)
+    ulp = np.maximum(np.abs(np.spacing(want.astype(np.float16)).astype(np.float64)), 2.0**-24)
+    assert np.all(np.abs(got[:, :K].astype(np.float64) - w16) <= ulp)
+    assert rel_rows(got[:, :K], want) <= 1e-3
+
+
+def test_dequantize_flags_bad_codes(gpu, ref):
+    torch, binding = gpu
+    codes, scales = synth.random_packed(32, 512, "bad")
+    for word, bit in ((7, 3 << 10), (256 + 40, 1 << 9)):
+        bad = codes.copy()
+        bad[384 * 2 + word] |= np.uint32(bit)
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        got = binding.itq3s_dequantize(to_dev(torch, bad.view(np.int32)), to_dev(torch, scales.view(np.int32)), 32, 512, status_flags=flags)
+        want, rflags = ref.dequantize(bad, scales, 32, 512, return_flags=True)
+        assert int(flags.item()) == rflags == binding.FLAG_BAD_CODE
+        assert rel_rows(got.cpu().numpy(), want) <= DEQ_TOL
+
+
+def test_quantize_dequantize_round_trip_error_bound(gpu, ref):
+    """Thm 2 on the GPU path: per block, ||w_hat - w||^2 <= sum_j max(d/2, |w'_j/d + z| - 1)^2 d^2."""
+    torch, binding = gpu
+    N, K = 64, 1024
+    W = synth.weights(N, K, "rt")
+    codes, scales = binding.itq3s_quantize(to_dev(torch, W))
+    What = binding.itq3s_dequantize(codes, scales, N, K).cpu().numpy().astype(np.float64)
+    s = u32(scales).reshape(-1, 4, 16)
+    for n in range(0, N, 7):
+        for b in range(4):
+            word = int(s[n // 16, b, n % 16])
+            d = float(np.array([word & 0xFFFF], np.uint16).view(np.float16)[0])
+            z = float(np.array([word >> 16], np.uint16).view(np.float16)[0])
+            wt = ref.forward_block(W[n, 256 * b : 256 * b + 256])
+            bound = np.sum((np.maximum(0.5, np.abs(wt / d + z) - 1.0) * d) ** 2)
+            err = np.sum((What[n, 256 * b : 256 * b + 256] - W[n, 256 * b : 256 * b + 256]) ** 2)
+            assert err <= bound * (1 + 1e-5)
+
+
+# ----------------------------------------------------------------------------------- matmul
+
+
+def run_matmul(torch, binding, ref, codes, scales, N, K, X, out_dtype=None, rows=None):
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    Y = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), dtype=out_dtype or torch.float32, status_flags=flags)
+    torch.cuda.synchronize()
+    assert int(flags.item()) == 0
+    Y = Y.float().cpu().numpy()
+    if rows is None:
+        want = ref.matmul(codes, scales, N, K, X)
+        return rel_rows(Y, want)
+    worst = 0.0
+    for n0, n1 in rows:
+        want = ref.matmul(codes, scales, N, K, X, rows=(n0, n1))[:, n0:n1]
+        worst = max(worst, rel_rows(Y[:, n0:n1], want))
+    return worst
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16])
+@pytest.mark.parametrize("N,K", [(16, 256), (48, 512), (1000, 1024), (2048, 2048), (272, 11008)])
+def test_matmul_small_m(gpu, ref, M, N, K):
+    torch, binding = gpu
+    if (N, K) == (2048, 2048):
+        W = synth.weights(N, K, "single", n_outlier_cols=4)
+        W[::97, 0] += 0.6  # a few blocks with non-zero zero-point
+        codes, scales, _ = ref.quantize(W)
+        X = synth.activations(M, K, "mm", outlier_frac=0.0 if M == 1 else 0.005)
+    else:
+        codes, scales = synth.random_packed(N, K, "mm", M, z_fraction=0.02)
+        X = synth.activations(M, K, "mm", N)
+    assert run_matmul(torch, binding, ref, codes, scales, N, K, X) <= MATMUL_TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(17, 48, 512), (64, 256, 1024), (130, 1000, 768), (200, 144, 2048), (512, 384, 4096)])
+def test_matmul_tiled_path(gpu, ref, M, N, K):
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "gemm", M, z_fraction=0.02)
+    X = synth.activations(M, K, "gemm", N)
+    assert run_matmul(torch, binding, ref, codes, scales, N, K, X) <= MATMUL_TOL
+
+
+def test_matmul_quantized_weights_tiled_path(gpu, ref):
+    torch, binding = gpu
+    N, K, M = 512, 2048, 96
+    W = synth.weights(N, K, "gemmq")
+    W[::31, 256] -= 0.8
+    codes, scales, _ = ref.quantize(W)
+    X = synth.activations(M, K, "gemmq")
+    assert run_matmul(torch, binding, ref, codes, scales, N, K, X) <= MATMUL_TOL
+    # and the product really approximates the unquantized one at 3-bit accuracy (sanity, loose)
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    Y = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X)).cpu().numpy().astype(np.float64)
+    exact = X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.linalg.norm(Y - exact) / np.linalg.norm(exact) < 0.6
+
+
+@pytest.mark.parametrize("M", [1, 16, 40])
+def test_matmul_fp16_output_and_strides(gpu, ref, M):
+    torch, binding = gpu
+    N, K = 304, 1024
+    codes, scales = synth.random_packed(N, K, "f16out", M)
+    X = synth.activations(M, K, "f16out")
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    xbuf = torch.zeros((M, K + 16), dtype=torch.float16, device="cuda")
+    xbuf[:, :K] = to_dev(torch, X)
+    ybuf = torch.full((M, N + 5), 7.0, dtype=torch.float16, device="cuda")
+    binding.itq3s_matmul(cd, sd, N, K, xbuf[:, :K], out=ybuf[:, :N])
+    got = ybuf.float().cpu().numpy()
+    assert np.all(got[:, N:] == 7.0)
+    want = ref.matmul(codes, scales, N, K, X)
+    assert rel_rows(got[:, :N], want) <= MATMUL_TOL
+
+
+def test_matmul_is_deterministic(gpu, ref):
+    torch, binding = gpu
+    N, K = 4096, 4096
+    codes, scales = synth.random_packed(N, K, "det")
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    for M in (1, 8, 64):
+        X = to_dev(torch, synth.activations(M, K, "det"))
+        a = binding.itq3s_matmul(cd, sd, N, K, X).cpu().numpy()
+        b = binding.itq3s_matmul(cd, sd, N, K, X).cpu().numpy()
+        assert np.array_equal(a, b)
+
+
+def test_matmul_flags_high_plane(gpu, ref):
+    torch, binding = gpu
+    codes, scales = synth.random_packed(64, 512, "hp")
+    bad = codes.copy()
+    bad[384 * 3 + 256 + 77] |= np.uint32(1 << 20)
+    for M in (1, 32):
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        binding.itq3s_matmul(to_dev(torch, bad.view(np.int32)), to_dev(torch, scales.view(np.int32)), 64, 512,
+                             to_dev(torch, synth.activations(M, 512, "hp")), status_flags=flags)
+        assert int(flags.item()) == binding.FLAG_BAD_CODE
+
+
+def sample_row_ranges(N, count, seed):
+    rng = np.random.default_rng(seed)
+    starts = sorted(set([0, max(N - 16, 0)] + [int(v) for v in rng.integers(0, max(N - 16, 1), size=count)]))
+    return [(s, min(s + 16, N)) for s in starts]
+
+
+FULL = [
+    ("llama7b", 4096, 4096, (1, 8)),
+    ("llama7b", 11008, 4096, (1, 8)),
+    ("llama7b", 4096, 11008, (1, 8)),
+    ("llama70b", 8192, 8192, (1, 4, 16)),
+    ("llama70b", 28672, 8192, (1, 16)),
+    ("llama70b", 8192, 28672, (1, 16)),
+    ("llama70b", 1024, 8192, (1, 4, 16)),
+]
+
+
+@pytest.mark.parametrize("name,N,K,Ms", FULL)
+def test_matmul_full_size_sampled_rows(gpu, ref, name, N, K, Ms):
+    """The benchmark's shapes in the benchmark's launch configuration; the oracle recomputes a
+    sample of 16-row ranges (first, last and random ones) for every activation row."""
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, name, z_fraction=0.001)
+    for M in Ms:
+        X = synth.activations(M, K, name, N)
+        worst = run_matmul(torch, binding, ref, codes, scales, N, K, X, rows=sample_row_ranges(N, 6, N + K + M))
+        assert worst <= MATMUL_TOL, (N, K, M, worst)
+
+
+@pytest.mark.parametrize("N,K,M", [(14336, 4096, 512), (4096, 14336, 512), (14336, 4096, 2048)])
+def test_matmul_prefill_full_size_sampled(gpu, ref, N, K, M):
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "prefill", z_fraction=0.001)
+    X = synth.activations(M, K, "prefill", N)
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    Y = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), dtype=torch.float16)
+    torch.cuda.synchronize()
+    Y = Y.float().cpu().numpy()
+    rng = np.random.default_rng(N + M)
+    msel = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 14)]))
+    worst = 0.0
+    for n0, n1 in sample_row_ranges(N, 10, N + K):
+        want = ref.matmul(codes, scales, N, K, X[msel], rows=(n0, n1))[:, n0:n1]
+        worst = max(worst, np.max(np.linalg.norm(Y[msel][:, n0:n1] - want, axis=1) / np.linalg.norm(want, axis=1)))
+    assert worst <= MATMUL_TOL
+
+
+def test_end_to_end_config1(gpu, ref):
+    """Config 1 as one pipeline on the GPU: quantize -> matmul, against oracle quantize -> matmul."""
+    torch, binding = gpu
+    N = K = 2048
+    W = synth.weights(N, K, "single", n_outlier_cols=4)
+    X = synth.activations(1, K, "single", outlier_frac=0.0)
+    codes, scales = binding.itq3s_quantize(to_dev(torch, W))
+    Y = binding.itq3s_matmul(codes, scales, N, K, to_dev(torch, X)).cpu().numpy()
+    rc, rs, _ = ref.quantize(W)
+    assert np.array_equal(u32(codes), rc) and np.array_equal(u32(scales), rs)
+    assert rel_rows(Y, ref.matmul(rc, rs, N, K, X)) <= MATMUL_TOL
