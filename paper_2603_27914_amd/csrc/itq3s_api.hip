@@ -86,10 +86,12 @@ int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64
     const _Float16* Xh = static_cast<const _Float16*>(X);
     if (M <= itq3s::kGemvMaxM) {
         const int MP = pad_m(M);
+        if (itq3s::gemv_can_fuse(M, K))
+            return itq3s::launch_gemv(codes, scales, N, K, Xh, ldx, nullptr, M, MP, true, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
         float* S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.xt_bytes);
         int rc = itq3s::launch_rotate_frag(Xh, M, K, ldx, MP, Xt, S, st);
         if (rc != 0) return rc;
-        return itq3s::launch_gemv(codes, scales, N, K, Xt, S, M, MP, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+        return itq3s::launch_gemv(codes, scales, N, K, Xt, 0, S, M, MP, false, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
     }
     int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, st);
     if (rc != 0) return rc;

@@ -4,43 +4,53 @@
 //
 // with c = q+1 the stored code, x~ = H x the rotated activation chunk and S[m,b] = sum_j x~[m,b,j]
 // (so that sum_j (c-1-z) x~ is formed without ever touching a signed digit).  The packed weights are
-// read exactly once, with one 16-byte + one 8-byte + one 16-byte (scales) load per lane and tile;
+// read exactly once, with one 16-byte + one 8-byte + one 4-byte (scale) load per lane and tile;
 // nothing dequantized is written anywhere.
 //
-// Contraction: v_mfma_f32_16x16x32_f16.  A operand = 16 weight rows of a tile, B operand = x~ for up
-// to 16 activation rows.  A code c in {0,1,2} placed in bits 11:10 of a half is the number
-// c * 2^-14 (bit pattern c<<10: exponent field 0, 1, 2, mantissa 0), so two codes that sit 16 bits
-// apart in a low-plane word become a half2 with one shift and one mask; the factor 2^14 is applied
-// to the block sum together with d.
+// Contraction: v_mfma_f32_16x16x32_f16 with the activations as the A operand (rows = m) and 16
+// weight rows of a tile as the B operand (columns = n), so that every accumulator of a lane belongs
+// to the lane's own weight row and needs only that row's scale.  A code c in {0,1,2} placed in bits
+// 11:10 of a half is the number c * 2^-14 (bit pattern c<<10: exponent field 0, 1, 2, mantissa 0),
+// so two codes that sit 16 bits apart in a low-plane word become a half2 with one shift and one
+// mask; the factor 2^14 is applied to the block sum together with d.
 //
-// Work split: the grid is persistent, workgroup g owns a contiguous range of 16-row tiles and all of
-// K; inside a workgroup, wavefront w takes blocks b = w, w+W, ... of a staged chunk of x~, keeps the
-// B fragments of one block in registers and streams the (up to RT) row tiles of the current
-// sub-group past them.  Loads for the next D steps are in flight while the current one is multiplied
-// (ring of D+1 register buffers, main loop unrolled D+1 times so that every index is static).
+// Work split: workgroup g owns a contiguous range of at most RT 16-row tiles and all of K.  Inside
+// a workgroup, wavefront w takes blocks b = w, w+W, ...; no two wavefronts share a block, so each
+// prepares the x~ fragments of its own blocks by itself and the only barrier is the one before the
+// final cross-wavefront sum.  Two ways to get the fragments:
+//   kFused : the wavefront rotates its blocks of X itself (256-point butterflies across the 64 lanes)
+//            and parks the result in its private slice of LDS -- one launch per matmul;
+//   direct : a separate rotation kernel has written x~ in operand order to the workspace and the
+//            fragments are loaded from there next to the tiles (larger M or K).
+// Tile loads run D blocks ahead of the arithmetic through a ring of D+1 register buffers (loop
+// unrolled D+1 times so that ring indices are static).  Every load in the pipeline is issued
+// unconditionally -- steps past the end of a wavefront's list re-read tile 0, which is cached -- so
+// that the load counter alone, not a full drain, orders loads and use.
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
 namespace itq3s {
 
-constexpr int kGemvWaves = 8;                // wavefronts per workgroup
-constexpr int kChunkBytesMax = 64 * 1024;    // x~ chunk staged in LDS
+constexpr int kGemvWaves = 8;        // wavefronts per workgroup
+constexpr int kGemvMaxRT = 7;        // row tiles per workgroup, at most
+constexpr int kFusedMaxBlocks = 4;   // fused rotation: blocks per wavefront times MP, at most (more costs
+                                     // more than the separate rotation launch it saves)
 
 struct GemvArgs {
     const uint32_t* codes;
     const uint32_t* scales;
-    const _Float16* Xt;  // rotated activations, operand order, MP columns
-    const float* S;      // [KB][MP]
+    const _Float16* X;  // kFused: activations [M][ldx]; direct: rotated, operand order, MP columns
+    const float* S;     // direct only: [KB][MP]
     void* Y;
     uint32_t* flags;
-    int64_t N, ldy;
-    int NT, KB, KC, M, y_f16;
+    int64_t N, ldx, ldy;
+    int NT, KB, M, y_f16;
 };
 
 struct TileRegs {
     u32x4 lo;
     u32x2 hi;
-    u32x4 sc;
+    uint32_t sc;
 };
 
 __device__ __forceinline__ void load_tile(TileRegs& r, const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scales,
@@ -48,7 +58,7 @@ __device__ __forceinline__ void load_tile(TileRegs& r, const uint32_t* __restric
     const uint32_t* t = codes + tile * kTileWords;
     r.lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(t) + lane);
     r.hi = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(t + kTileLoWords) + lane);
-    r.sc = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(scales + tile * kTileRows) + (lane >> 4));
+    r.sc = __builtin_nontemporal_load(scales + tile * kTileRows + (lane & 15));
 }
 
 __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
@@ -56,8 +66,10 @@ __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, ui
     return __builtin_bit_cast(half8, u);
 }
 
-// 64 codes of this lane (one tile row, one quarter of the block) times the matching x~ fragments.
-__device__ __forceinline__ floatx4 tile_dot(const u32x4& lo, const half8 (&Bf)[8]) {
+// 64 codes of this lane (one tile row, one quarter of the block) against the matching x~ fragments:
+// returns sum_j c_j 2^-14 x~[m][j] for m = 4*(lane/16) + 0..3 and the lane's weight row; the MFMA
+// adds the four quarters of the block.
+__device__ __forceinline__ floatx4 tile_dot(const u32x4& lo, const half8 (&Xf)[8]) {
     constexpr uint32_t kMask = 0x0C000C00u;
     const uint32_t w[4] = {lo.x, lo.y, lo.z, lo.w};
     floatx4 c = {0.f, 0.f, 0.f, 0.f};
@@ -67,196 +79,235 @@ __device__ __forceinline__ floatx4 tile_dot(const u32x4& lo, const half8 (&Bf)[8
         // slots j and j+8 of the word -> bits 11:10 and 27:26
         half8 a0 = as_half8((v << 10) & kMask, (v << 8) & kMask, (v << 6) & kMask, (v << 4) & kMask);
         half8 a1 = as_half8((v << 2) & kMask, v & kMask, (v >> 2) & kMask, (v >> 4) & kMask);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, Bf[2 * i], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, Bf[2 * i + 1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf[2 * i], a0, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf[2 * i + 1], a1, c, 0, 0, 0);
     }
     return c;
 }
 
-template <int MP, int RT, int D, int W>
-__global__ __launch_bounds__(W * 64) void gemv_kernel(const GemvArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int KC = a.KC, KB = a.KB;
-    _Float16* xs = reinterpret_cast<_Float16*>(smem);                                  // KC * MP * 256 halves
-    float* ss = reinterpret_cast<float*>(smem + (size_t)KC * MP * 512);                // KC * MP floats
-    float* red = reinterpret_cast<float*>(smem + (size_t)KC * MP * 512 + (((size_t)KC * MP * 4 + 15) & ~(size_t)15));  // W*256 floats
+// value of lane (l ^ MASK): data-parallel-primitive moves inside a row of 16 lanes, LDS crossbar
+// (no memory access) across rows
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+    int x = __builtin_bit_cast(int, v);
+    if constexpr (MASK == 1) x = __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false);       // quad_perm [1,0,3,2]
+    else if constexpr (MASK == 2) x = __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false);  // quad_perm [2,3,0,1]
+    else if constexpr (MASK == 4) {  // l^7 (mirror in 8) then l^3 (reverse in 4)
+        x = __builtin_amdgcn_update_dpp(x, x, 0x141, 0xf, 0xf, false);
+        x = __builtin_amdgcn_update_dpp(x, x, 0x1B, 0xf, 0xf, false);
+    } else if constexpr (MASK == 8) {  // l^15 (mirror in 16) then l^7
+        x = __builtin_amdgcn_update_dpp(x, x, 0x140, 0xf, 0xf, false);
+        x = __builtin_amdgcn_update_dpp(x, x, 0x141, 0xf, 0xf, false);
+    } else x = __shfl_xor(x, MASK, 64);
+    return __builtin_bit_cast(float, x);
+}
 
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int g = lane >> 4, mcol = lane & 15, mm = mcol & (MP - 1);
+template <int MASK>
+__device__ __forceinline__ void butterfly_stage(float (&v)[4], int lane) {
+    const bool upper = (lane & MASK) != 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float p = lane_xor<MASK>(v[i]);
+        v[i] = upper ? (p - v[i]) : (v[i] + p);
+    }
+}
+
+// x~ = H x for one 256-chunk held as elements 4l..4l+3 per lane, rounded to fp16, scattered into
+// operand order at `dst` (256*MP halves: index ((t*4 + g)*MP + m)*8 + i); returns sum of the rounded
+// values in every lane.
+template <int MP>
+__device__ __forceinline__ float rotate_to_lds(u32x2 raw, int lane, int m, _Float16* dst) {
+    const half4 h = __builtin_bit_cast(half4, raw);
+    float v[4] = {(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+    const float t0 = v[0] + v[1], t1 = v[0] - v[1], t2 = v[2] + v[3], t3 = v[2] - v[3];
+    v[0] = t0 + t2; v[2] = t0 - t2; v[1] = t1 + t3; v[3] = t1 - t3;
+    butterfly_stage<1>(v, lane);
+    butterfly_stage<2>(v, lane);
+    butterfly_stage<4>(v, lane);
+    butterfly_stage<8>(v, lane);
+    butterfly_stage<16>(v, lane);
+    butterfly_stage<32>(v, lane);
+    _Float16 r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = (_Float16)(v[i] * 0.0625f);
+    float s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
+    s += lane_xor<1>(s); s += lane_xor<2>(s); s += lane_xor<4>(s); s += lane_xor<8>(s); s += lane_xor<16>(s); s += lane_xor<32>(s);
+    // element e = 4l + j: quarter g = e>>6, word w = (e>>4)&3, slot = e&15 = 4q + j with q = l&3;
+    // MFMA step t = 2w + ((slot&7)>>2) = 2w + (q&1), position i = 2(slot&3) + (slot>>3) = 2j + (q>>1)
+    const int g = lane >> 4, w = (lane >> 2) & 3, q = lane & 3;
+    const int t = 2 * w + (q & 1), i0 = q >> 1;
+    _Float16* p = dst + ((t * 4 + g) * MP + m) * 8 + i0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) p[2 * j] = r[j];
+    return s;
+}
+
+template <int MP, int RT, int D, bool kFused>
+__global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a) {
+    constexpr int W = kGemvWaves;
+    constexpr int NB = D + 1;
+    constexpr int NBX = kFusedMaxBlocks / MP;  // kFused: blocks per wavefront, at most
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int KB = a.KB;
+
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // wave-uniform, in an SGPR
+    const int g = lane >> 4, r16 = lane & 15, mm = r16 & (MP - 1);
     const int nt_begin = (int)(((int64_t)blockIdx.x * a.NT) / gridDim.x);
     const int nt_end = (int)(((int64_t)(blockIdx.x + 1) * a.NT) / gridDim.x);
-    const int n_sg = (nt_end - nt_begin + RT - 1) / RT;
-    const int n_chunks = (KB + KC - 1) / KC;
-    if (n_sg == 0) return;
+    const int cnt = nt_end - nt_begin;  // RT-1 or RT row tiles (the host picks the grid that way)
+    const bool full = RT == 1 || cnt == RT;
+    const int nb = KB > wave ? (KB - wave + W - 1) / W : 0;  // blocks of this wavefront: b = wave + j*W
 
-    // Step = (sub-group sg, chunk c, j): this wavefront's block b = c*KC + j*W + wave (if inside the
-    // chunk) against row tiles nt_begin + sg*RT + [0, RT).  Every wavefront runs the same number of
-    // steps so that the barriers below line up.
-    struct Step {
-        int sg, c, j;
-    };
-    auto steps_in_chunk = [&](int c) { return (min(KC, KB - c * KC) + W - 1) / W; };
-    auto advance = [&](Step& s) {
-        if (++s.j == steps_in_chunk(s.c)) {
-            s.j = 0;
-            if (++s.c == n_chunks) { s.c = 0; ++s.sg; }
-        }
-    };
-    auto issue = [&](const Step& s, TileRegs (&buf)[RT]) {
-        if (s.sg >= n_sg) return;
-        const int b = s.c * KC + s.j * W + wave;
-        if (b >= min((s.c + 1) * KC, KB)) return;
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            const int nt = nt_begin + s.sg * RT + rt;
-            if (nt < nt_end) load_tile(buf[rt], a.codes, a.scales, (int64_t)nt * KB + b, lane);
-        }
-    };
+    // LDS: kFused: per wavefront NBX*MP*256 halves of x~, then NBX*MP sums per wavefront; then the
+    // reduction buffer
+    _Float16* xs = reinterpret_cast<_Float16*>(smem) + (size_t)wave * (kFused ? NBX * MP * 256 : 0);
+    float* ss = reinterpret_cast<float*>(smem + (kFused ? (size_t)W * NBX * MP * 512 : 0)) + wave * NBX * MP;
+    float* red = reinterpret_cast<float*>(smem + (kFused ? (size_t)W * NBX * MP * (512 + 4) : 0));  // W*RT*MP*16 floats
 
     floatx4 acc[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) acc[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
     uint32_t bad = 0;
 
-    // x~ chunk c (and its S values): global -> registers, then registers -> LDS between two barriers.
-    constexpr int kStageMax = kChunkBytesMax / (W * 64 * 16);
-    u32x4 stage[kStageMax];
-#pragma unroll
-    for (int i = 0; i < kStageMax; ++i) stage[i] = u32x4{0u, 0u, 0u, 0u};
-    float stage_s = 0.f;
-    auto stage_load = [&](int c) {
-        const int c_len = min(KC, KB - c * KC);
-        const u32x4* src = reinterpret_cast<const u32x4*>(a.Xt + (size_t)c * KC * MP * 256);
-        const int n16 = c_len * MP * 32;  // 16-byte units
-#pragma unroll
-        for (int i = 0; i < kStageMax; ++i) {
-            const int idx = i * (W * 64) + threadIdx.x;
-            if (idx < n16) stage[i] = src[idx];
-        }
-        if ((int)threadIdx.x < c_len * MP) stage_s = a.S[(size_t)c * KC * MP + threadIdx.x];
+    struct Slot {
+        TileRegs t[RT];
+        half8 xf[kFused ? 1 : 8];
+        floatx4 sv;
     };
-    auto stage_publish = [&](int c) {
-        const int c_len = min(KC, KB - c * KC);
-        const int n16 = c_len * MP * 32;
-        __syncthreads();  // everyone is done with the previous chunk
-#pragma unroll
-        for (int i = 0; i < kStageMax; ++i) {
-            const int idx = i * (W * 64) + threadIdx.x;
-            if (idx < n16) reinterpret_cast<u32x4*>(xs)[idx] = stage[i];
-        }
-        if ((int)threadIdx.x < c_len * MP) ss[threadIdx.x] = stage_s;
-        __syncthreads();
-    };
+    Slot ring[NB];
 
-    auto run_step = [&](const Step& s, const Step& ahead, const TileRegs (&cur)[RT], TileRegs (&nxt)[RT], bool first) {
-        // the very first chunk is staged before the loop; later chunks (only when x~ does not fit
-        // in one chunk) are staged here, loads issued ahead of the prefetch
-        const bool new_chunk = s.j == 0 && n_chunks > 1 && !first;
-        const int c_len = min(KC, KB - s.c * KC);
-        if (new_chunk) stage_load(s.c);
-        issue(ahead, nxt);  // prefetch the step D ahead into the buffer that was consumed last
-        if (new_chunk) stage_publish(s.c);
-        // (d) multiply
-        const int bl = s.j * W + wave;
-        if (bl < c_len) {
-            half8 Bf[8];
+    // loads of step j (block wave + j*W against all row tiles of the workgroup); past the end of
+    // the list, and for the missing last row tile, tile 0 / block 0 stand in (never used)
+    auto issue = [&](Slot& s, int j) {
+        const bool live = j < nb;
+        const int b = wave + j * W;
+        const int64_t t0 = live ? (int64_t)nt_begin * KB + b : 0;
+        const int64_t step = live ? KB : 0;
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                Bf[t] = *reinterpret_cast<const half8*>(xs + ((size_t)((bl * 8 + t) * 4 + g) * MP + mm) * 8);
-            const float sv = ss[bl * MP + mm];
+        for (int rt = 0; rt < RT - 1; ++rt) load_tile(s.t[rt], a.codes, a.scales, t0 + rt * step, lane);
+        load_tile(s.t[RT - 1], a.codes, a.scales, full ? t0 + (RT - 1) * step : 0, lane);
+        if constexpr (!kFused) {
+            const int bb = live ? b : 0;
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                const int nt = nt_begin + s.sg * RT + rt;
-                if (nt < nt_end) {
-                    const TileRegs& tr = cur[rt];
-                    const floatx4 c = tile_dot(tr.lo, Bf);
-                    bad |= tr.hi.x | tr.hi.y;
-                    const uint32_t sw[4] = {tr.sc.x, tr.sc.y, tr.sc.z, tr.sc.w};
-                    const uint32_t zbits = (sw[0] | sw[1] | sw[2] | sw[3]) >> 16;
-                    if (__builtin_amdgcn_ballot_w64(zbits != 0u) == 0ull) {
+            for (int t = 0; t < 8; ++t) s.xf[t] = *reinterpret_cast<const half8*>(a.X + ((size_t)((bb * 8 + t) * 4 + g) * MP + mm) * 8);
+            if constexpr (MP >= 4) {
+                s.sv = *reinterpret_cast<const floatx4*>(a.S + (size_t)bb * MP + ((4 * g) & (MP - 1)));
+            } else {
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            acc[rt][i] = __builtin_fmaf(f16_bits_to_f32(sw[i] & 0xffffu), __builtin_fmaf(c[i], 16384.0f, -sv), acc[rt][i]);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float zf = 1.0f + f16_bits_to_f32(sw[i] >> 16);
-                            acc[rt][i] = __builtin_fmaf(f16_bits_to_f32(sw[i] & 0xffffu), __builtin_fmaf(c[i], 16384.0f, -(zf * sv)), acc[rt][i]);
-                        }
-                    }
-                }
+                for (int i = 0; i < 4; ++i) s.sv[i] = a.S[(size_t)bb * MP + ((4 * g + i) & (MP - 1))];
             }
-        }
-        // (e) end of a sub-group: add the W partial sums, store Y
-        if (s.c == n_chunks - 1 && s.j == steps_in_chunk(s.c) - 1) {
-            constexpr int kPerRound = 16 / MP;  // row tiles per round through the 16 KB reduction buffer
-#pragma unroll
-            for (int r0 = 0; r0 < RT; r0 += kPerRound) {
-                __syncthreads();
-#pragma unroll
-                for (int rr = 0; rr < kPerRound; ++rr) {
-                    const int rt = r0 + rr;
-                    if (rt < RT && mcol < MP) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) red[((wave * kPerRound + rr) * 16 + 4 * g + i) * MP + mcol] = acc[rt][i];
-                    }
-                }
-                __syncthreads();
-                // outputs of this round: kPerRound tiles x 16 rows x MP columns; thread -> (m, rr, row)
-                for (int o = threadIdx.x; o < kPerRound * 16 * MP; o += W * 64) {
-                    const int row = o & 15, rr = (o >> 4) % kPerRound, m = o / (16 * kPerRound);
-                    const int rt = r0 + rr;
-                    const int nt = nt_begin + s.sg * RT + rt;
-                    const int64_t n = (int64_t)nt * 16 + row;
-                    if (rt < RT && nt < nt_end && n < a.N && m < a.M) {
-                        float sum = 0.f;
-#pragma unroll
-                        for (int wv = 0; wv < W; ++wv) sum += red[((wv * kPerRound + rr) * 16 + row) * MP + m];
-                        if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)sum;
-                        else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = sum;
-                    }
-                }
-            }
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt) acc[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
         }
     };
 
-    constexpr int NB = D + 1;
-    TileRegs ring[NB][RT];
-    Step s{0, 0, 0}, ahead{0, 0, 0};
-    stage_load(0);
+    auto compute = [&](const Slot& s, int j) {
+        half8 Xf[8];
+        floatx4 sv;
+        if constexpr (kFused) {
+            const _Float16* xb = xs + (size_t)j * MP * 256;
 #pragma unroll
-    for (int k = 0; k < D; ++k) {
-        issue(ahead, ring[k]);
-        advance(ahead);
+            for (int t = 0; t < 8; ++t) Xf[t] = *reinterpret_cast<const half8*>(xb + ((t * 4 + g) * MP + mm) * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
+        } else {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) Xf[t] = s.xf[t];
+            sv = s.sv;
+        }
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            if (rt < RT - 1 || full) {
+                const TileRegs& tr = s.t[rt];
+                const floatx4 c = tile_dot(tr.lo, Xf);
+                bad |= tr.hi.x | tr.hi.y;
+                const float d = f16_bits_to_f32(tr.sc & 0xffffu);
+                const float z1 = 1.0f + f16_bits_to_f32(tr.sc >> 16);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[rt][i] = __builtin_fmaf(d, __builtin_fmaf(c[i], 16384.0f, -(z1 * sv[i])), acc[rt][i]);
+            }
+        }
+    };
+
+    // ---- activations of this wavefront's blocks first (kFused), then the first D steps of tiles
+    u32x2 xraw[kFused ? NBX * MP : 1];
+    if constexpr (kFused) {
+#pragma unroll
+        for (int j = 0; j < NBX; ++j) {
+            const int b = j < nb ? wave + j * W : 0;
+#pragma unroll
+            for (int m = 0; m < MP; ++m) {
+                const int mr = m < a.M ? m : 0;
+                xraw[j * MP + m] = *reinterpret_cast<const u32x2*>(a.X + (size_t)mr * a.ldx + (size_t)b * kBlock + 4 * lane);
+            }
+        }
     }
-    stage_publish(0);
-    bool done = false, first = true;
-    while (!done) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue(ring[d], d);
+    if constexpr (kFused) {
+#pragma unroll
+        for (int j = 0; j < NBX; ++j) {
+            if (j < nb) {
+#pragma unroll
+                for (int m = 0; m < MP; ++m) {
+                    u32x2 raw = xraw[j * MP + m];
+                    if (m >= a.M) raw = u32x2{0u, 0u};
+                    const float s = rotate_to_lds<MP>(raw, lane, m, xs + (size_t)j * MP * 256);
+                    if (lane == 0) ss[j * MP + m] = s;
+                }
+            }
+        }
+    }
+
+    // ---- steady state: NB steps per trip, every prefetch is a live step
+    int bi = 0;
+    for (; bi + NB + D <= nb; bi += NB) {
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
-            if (!done) {
-                run_step(s, ahead, ring[k], ring[(k + D) % NB], first);
-                first = false;
-                advance(s);
-                advance(ahead);
-                done = s.sg >= n_sg;
-            }
+            issue(ring[(k + D) % NB], bi + k + D);
+            compute(ring[k], bi + k);
+        }
+    }
+    // ---- tail: fewer than NB + D steps left
+#pragma unroll
+    for (int k = 0; k < NB + D - 1; ++k) {
+        if (bi + k >= nb) break;  // straight line up to the exit: no merge point between steps
+        issue(ring[(k + D) % NB], bi + k + D);
+        compute(ring[k % NB], bi + k);
+    }
+
+    // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]
+    __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * g + i < MP) red[((wave * RT + rt) * MP + 4 * g + i) * 16 + r16] = acc[rt][i];
+    __syncthreads();
+    for (int o = threadIdx.x; o < RT * 16 * MP; o += W * 64) {
+        const int rr = o % (RT * 16), m = o / (RT * 16);  // rr = rt*16 + r: consecutive threads, consecutive n
+        const int rt = rr >> 4;
+        const int64_t n = (int64_t)nt_begin * 16 + rr;
+        if (rt < cnt && n < a.N && m < a.M) {
+            float sum = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < W; ++wv) sum += red[((wv * RT + rt) * MP + m) * 16 + (rr & 15)];
+            if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)sum;
+            else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = sum;
         }
     }
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
-template <int MP, int RT, int D, int W>
-static int launch_one(const GemvArgs& a, int grid, size_t lds, hipStream_t stream) {
-    auto kern = gemv_kernel<MP, RT, D, W>;
+template <int MP, int RT, int D, bool kFused>
+static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
+    auto kern = gemv_kernel<MP, RT, D, kFused>;
     static bool lds_limit_raised = false;  // once per instantiation: allow up to the 160 KB of a CU
     if (!lds_limit_raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
         lds_limit_raised = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(W * 64), lds, stream, a);
+    const size_t lds = (kFused ? (size_t)kGemvWaves * (kFusedMaxBlocks / MP) * MP * (512 + 4) : 0) + (size_t)kGemvWaves * RT * MP * 16 * 4;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
@@ -270,33 +321,72 @@ static int cu_count() {
     return n;
 }
 
-template <int MP>
-static int launch_mp(GemvArgs a, hipStream_t stream) {
-    constexpr int W = kGemvWaves;
-    // chunk of x~ kept in LDS
-    const int kc_cap = kChunkBytesMax / (MP * 512);
-    a.KC = a.KB < kc_cap ? a.KB : kc_cap;
-    const size_t lds = (size_t)a.KC * MP * 512 + (((size_t)a.KC * MP * 4 + 15) & ~(size_t)15) + (size_t)W * 256 * 4;
-    const int grid = a.NT < cu_count() ? a.NT : cu_count();
-    // row tiles per workgroup decide how many tiles one step covers; keep about 8 tiles in flight
-    const int per_wg = (a.NT + grid - 1) / grid;
-    if (per_wg <= 1) return launch_one<MP, 1, 8, W>(a, grid, lds, stream);
-    if (per_wg == 2) return launch_one<MP, 2, 4, W>(a, grid, lds, stream);
-    if (per_wg == 3) return launch_one<MP, 3, 3, W>(a, grid, lds, stream);
-    return launch_one<MP, 4, 2, W>(a, grid, lds, stream);
+// Row tiles per workgroup and prefetch depth: about 8 tiles in flight per wavefront, but never deeper
+// than the shortest wavefront's list of blocks (deeper would only add stand-in loads), and shallow
+// enough that the ring fits the register file (the direct path keeps the x~ fragments in the ring too).
+template <int MP, bool kFused>
+static int launch_shape(const GemvArgs& a, int grid, int rt, int nb_min, hipStream_t stream) {
+    const int dmax = nb_min < 1 ? 1 : nb_min;
+    switch (rt) {
+        case 1:
+            if constexpr (kFused) {
+                if (dmax >= 8) return launch_one<MP, 1, 8, kFused>(a, grid, stream);
+            }
+            if (dmax >= 4) return launch_one<MP, 1, 4, kFused>(a, grid, stream);
+            if (dmax >= 2) return launch_one<MP, 1, 2, kFused>(a, grid, stream);
+            return launch_one<MP, 1, 1, kFused>(a, grid, stream);
+        case 2:
+            if constexpr (kFused) {
+                if (dmax >= 4) return launch_one<MP, 2, 4, kFused>(a, grid, stream);
+            }
+            if (dmax >= 2) return launch_one<MP, 2, 2, kFused>(a, grid, stream);
+            return launch_one<MP, 2, 1, kFused>(a, grid, stream);
+        case 3:
+            if (dmax >= 2) return launch_one<MP, 3, 2, kFused>(a, grid, stream);
+            return launch_one<MP, 3, 1, kFused>(a, grid, stream);
+        case 4:
+            if constexpr (kFused && MP <= 2) {
+                if (dmax >= 2) return launch_one<MP, 4, 2, kFused>(a, grid, stream);
+            }
+            return launch_one<MP, 4, 1, kFused>(a, grid, stream);
+        case 5: return launch_one<MP, 5, 1, kFused>(a, grid, stream);
+        case 6: return launch_one<MP, 6, 1, kFused>(a, grid, stream);
+        default: return launch_one<MP, 7, 1, kFused>(a, grid, stream);
+    }
 }
 
-int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const float* S, int64_t M,
-                int MP, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
+bool gemv_can_fuse(int64_t M, int64_t K) {
+    int mp = 1;
+    while (mp < M) mp <<= 1;
+    const int64_t nb_max = (K / kBlock + kGemvWaves - 1) / kGemvWaves;
+    return mp <= 4 && nb_max * mp <= kFusedMaxBlocks;
+}
+
+int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, const float* S,
+                int64_t M, int MP, bool fused, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
     GemvArgs a;
-    a.codes = codes; a.scales = scales; a.Xt = Xt; a.S = S; a.Y = Y; a.flags = flags;
-    a.N = N; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.KC = 0; a.M = (int)M; a.y_f16 = y_f16;
+    a.codes = codes; a.scales = scales; a.X = X; a.S = S; a.Y = Y; a.flags = flags;
+    a.N = N; a.ldx = ldx; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
+    // one workgroup per CU if that leaves at most kGemvMaxRT row tiles each, else more workgroups
+    const int max_rt = kGemvMaxRT;
+    int grid = a.NT < cu_count() ? a.NT : cu_count();
+    if ((a.NT + grid - 1) / grid > max_rt) grid = (a.NT + max_rt - 1) / max_rt;
+    const int rt = (a.NT + grid - 1) / grid;  // every workgroup gets rt or rt-1 row tiles
+    const int nb_min = a.KB / kGemvWaves;
+    if (fused) {
+        switch (MP) {
+            case 1: return launch_shape<1, true>(a, grid, rt, nb_min, stream);
+            case 2: return launch_shape<2, true>(a, grid, rt, nb_min, stream);
+            case 4: return launch_shape<4, true>(a, grid, rt, nb_min, stream);
+        }
+        return -2;
+    }
     switch (MP) {
-        case 1: return launch_mp<1>(a, stream);
-        case 2: return launch_mp<2>(a, stream);
-        case 4: return launch_mp<4>(a, stream);
-        case 8: return launch_mp<8>(a, stream);
-        case 16: return launch_mp<16>(a, stream);
+        case 1: return launch_shape<1, false>(a, grid, rt, nb_min, stream);
+        case 2: return launch_shape<2, false>(a, grid, rt, nb_min, stream);
+        case 4: return launch_shape<4, false>(a, grid, rt, nb_min, stream);
+        case 8: return launch_shape<8, false>(a, grid, rt, nb_min, stream);
+        case 16: return launch_shape<16, false>(a, grid, rt, nb_min, stream);
     }
     return -2;
 }

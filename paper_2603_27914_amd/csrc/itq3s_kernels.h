@@ -25,8 +25,13 @@ int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int
 // Rotated activations for the tiled path: Xt[m][k] row-major, row stride K.
 int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, hipStream_t stream);
 
-int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const float* S, int64_t M,
-                int MP, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+// True if the streaming kernel can rotate the activations itself (one launch, no workspace use).
+bool gemv_can_fuse(int64_t M, int64_t K);
+
+// fused: X = activations [M][ldx], S unused.  Otherwise X = rotated activations in operand order with
+// MP columns (from launch_rotate_frag), ldx unused, S = their block sums.
+int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, const float* S,
+                int64_t M, int MP, bool fused, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
 
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
                 int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
