@@ -9,7 +9,12 @@ re-read from a cache); `--workload llama70b_decode` runs the 80-layer 70B-shaped
 Weights are synthetic (Student-t, see paper_2603_27914_amd/synth.py), generated on the device and
 packed by itq3s_quantize, which is timed as well.
 
-Prints ONE JSON line.  `value` = packed-weight bytes streamed per second over the whole step.
+Prints ONE JSON line.  `value` = packed-weight bytes streamed per second over the whole step
+(wall clock over the replayed graph, launch gaps included).  `roofline` prices the streaming
+contraction kernel alone: algorithmic bytes of a call over the kernel's own duration, which
+itq3s_matmul_timed reads from HIP events attached to the kernel's dispatch, averaged over one more
+pass through every tensor of the step (the same quantity rocprofv3 --kernel-trace --stats lists as
+the kernel's average duration).
 """
 import argparse
 import json
@@ -24,6 +29,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
+
+# HBM traffic of the streaming kernel per launch, averaged over the step's launches, from two
+# rocprofv3 --pmc passes over this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
+# counter shows for copy_leg's 1 GiB copy; the summaries and the commands are under profiles/.
+MEASURED_TRAFFIC = {}
 
 WORKLOADS = {
     # name: (layers, [(tensor, N, K, copies)], M)
@@ -67,7 +77,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
-    ap.add_argument("--no-extras", action="store_true", help="skip the per-shape, prefill and CPU-oracle legs")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
+    ap.add_argument("--legs", default="per_shape,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -146,10 +157,23 @@ def main():
     step_alg = sum(alg_bytes(N, K, M) for N, K, *_ in tensors)
     value = step_packed / (ms_per_step * 1e-3) / 1e9
     calls = len(tensors)
-    # dominant kernel = the streaming contraction, one launch per call; average duration from the
-    # HIP events that bracket the timed region on the launch stream
-    avg_launch_ms = ev_ms / (args.steps * calls)
+    # dominant kernel = the streaming contraction (gemv_kernel), one launch per call: its duration by
+    # the events attached to each dispatch, one pass over the step's tensors in step order (every
+    # tensor comes from HBM: 2.5 GB lie between two uses of the same one)
+    kern_ms = {}
+    for N, K, codes, scales, li, ti in tensors:
+        _, ms = binding.itq3s_matmul_timed(codes, scales, N, K, xs[K], out=ys[N], workspace=ws)
+        kern_ms.setdefault((N, K), []).append(ms)
+    all_ms = [m for v in kern_ms.values() for m in v]
+    avg_launch_ms = sum(all_ms) / len(all_ms)
     achieved = (step_alg / calls) / (avg_launch_ms * 1e-3) / 1e9
+    per_kernel = []
+    for (N, K), v in kern_ms.items():
+        v = sorted(v)
+        med = v[len(v) // 2]
+        per_kernel.append({"N": N, "K": K, "launches": len(v), "us_mean": round(1e3 * sum(v) / len(v), 3), "us_median": round(1e3 * med, 3),
+                           "us_min": round(1e3 * v[0], 3), "GBps_mean": round(alg_bytes(N, K, M) / (sum(v) / len(v) * 1e-3) / 1e9, 1)})
+    traffic = MEASURED_TRAFFIC.get(args.workload) if layers == WORKLOADS[args.workload][0] else None
 
     out = {
         "metric": "ITQ3_S GEMV effective HBM GB/s on packed-weight bytes @M=1",
@@ -176,17 +200,26 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "traffic": traffic,
             "avg_launch_us": round(avg_launch_ms * 1e3, 3),
             "alg_bytes_per_launch": int(step_alg / calls),
+            "launches_timed": len(all_ms),
+            "per_kernel": per_kernel,
+            "step_wall_us_per_call": round(ev_ms / (args.steps * calls) * 1e3, 3),
         },
         "quantize": {"GBps": round(q_bytes / (q_ms * 1e-3) / 1e9, 1), "bytes": q_bytes, "ms": round(q_ms, 2), "frac_of_hbm_peak": round(q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
     }
 
-    if not args.no_extras:
+    legs = [] if args.no_extras else [x for x in args.legs.split(",") if x]
+    if "per_shape" in legs:
         out["per_shape"] = per_shape_leg(torch, binding, tensors, layer, gen)
+    if "prefill" in legs:
         out["prefill"] = prefill_leg(torch, binding, synth, gen)
+    if "dequantize" in legs:
         out["dequantize"] = dequantize_leg(torch, binding, tensors)
+    if "copy" in legs:
+        out["copy_ceiling"] = copy_leg(torch)
+    if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline_leg(torch, binding, tensors, layer, xs, M)
     print(json.dumps(out))
 
@@ -204,9 +237,29 @@ def time_calls(torch, fn, n_iter, warm=3):
     return e0.elapsed_time(e1) / n_iter
 
 
+def graph_time(torch, fn, n_calls, reps=10):
+    """fn() enqueues n_calls library calls; capture once, replay, -> milliseconds per call."""
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    for _ in range(3):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / (reps * n_calls)
+
+
 def per_shape_leg(torch, binding, tensors, layer, gen):
-    """Each shape on its own, cycling through all resident copies of that shape (so the weights
-    come from HBM, not from a cache), for M = 1 and a batched M."""
+    """Each shape on its own for M = 1 and M = 8, as a replayed graph: cycling through all resident
+    copies of that shape (weights come from HBM), and on one copy only (weights stay in the 256 MB
+    last-level cache; labelled as such)."""
     res = []
     for ti, (name, N, K, copies) in enumerate(layer):
         same = [t for t in tensors if t[5] == ti]
@@ -215,12 +268,14 @@ def per_shape_leg(torch, binding, tensors, layer, gen):
             Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
             ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
 
-            def run():
-                for N_, K_, codes, scales, *_ in same:
+            def run(which):
+                for N_, K_, codes, scales, *_ in which:
                     binding.itq3s_matmul(codes, scales, N_, K_, X, out=Y, workspace=ws)
 
-            ms = time_calls(torch, run, 5) / len(same)
-            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 2), "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1), "copies": len(same)})
+            ms = graph_time(torch, lambda: run(same), len(same))
+            ms_hot = graph_time(torch, lambda: run(same[:1] * 16), 16)
+            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 2), "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1),
+                        "copies": len(same), "us_cache_resident": round(ms_hot * 1e3, 2)})
     return res
 
 
@@ -247,6 +302,16 @@ def dequantize_leg(torch, binding, tensors):
     ms = time_calls(torch, lambda: binding.itq3s_dequantize(codes, scales, N, K, out=out), 10)
     nbytes = packed_bytes(N, K) + N * K * 4
     return {"N": N, "K": K, "us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+
+
+def copy_leg(torch):
+    """A plain device-to-device copy of known size: the practical ceiling next to the 8 TB/s peak, and
+    the kernel whose known traffic calibrates the FETCH_SIZE / WRITE_SIZE counters."""
+    n = 1 << 28  # 1 GiB of fp32 read + 1 GiB written
+    src = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    ms = time_calls(torch, lambda: dst.copy_(src), 10)
+    return {"bytes_read": 4 * n, "bytes_written": 4 * n, "us": round(ms * 1e3, 1), "GBps_read_plus_write": round(8 * n / (ms * 1e-3) / 1e9, 1)}
 
 
 def cpu_baseline_leg(torch, binding, tensors, layer, xs, M):

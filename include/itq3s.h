@@ -99,6 +99,15 @@ int itq3s_matmul(const uint32_t *codes, const uint32_t *scales, int64_t N, int64
                  void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
                  void *stream);
 
+/* Measurement aid: itq3s_matmul with the same arguments, after which the call WAITS for the work and
+ * stores in *kernel_ms (HOST pointer) the duration of the contraction kernel alone (the streaming
+ * kernel for M <= 16, the tiled kernel otherwise; not the activation-rotation launch in front of it,
+ * not launch gaps), taken from HIP events attached to that kernel's dispatch.  Creates and destroys
+ * two events per call and is not thread-safe: not for production loops, not capturable in a graph. */
+int itq3s_matmul_timed(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
+                       int64_t ldx, void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes,
+                       uint32_t *status_flags, void *stream, float *kernel_ms);
+
 /* Static text for a status code.  Never NULL. */
 const char *itq3s_strerror(int status);
 

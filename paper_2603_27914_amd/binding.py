@@ -22,6 +22,7 @@ EXPORTS = [
     "itq3s_quantize",
     "itq3s_dequantize",
     "itq3s_matmul",
+    "itq3s_matmul_timed",
     "itq3s_strerror",
     "itq3s_version",
 ]
@@ -53,6 +54,8 @@ def lib():
         L.itq3s_dequantize.argtypes = [vp, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul.restype = ci
         L.itq3s_matmul.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
+        L.itq3s_matmul_timed.restype = ci
+        L.itq3s_matmul_timed.argtypes = L.itq3s_matmul.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_strerror.restype = ctypes.c_char_p
         L.itq3s_strerror.argtypes = [ci]
         L.itq3s_version.restype = ci
@@ -130,7 +133,14 @@ def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_
     return out
 
 
-def itq3s_matmul(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None):
+def itq3s_matmul_timed(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None):
+    """itq3s_matmul, then wait; -> (Y, milliseconds the contraction kernel ran by the GPU's clock)."""
+    ms = ctypes.c_float(0.0)
+    out = itq3s_matmul(codes, scales, N, K, X, out, dtype, workspace, status_flags, _timed=ms)
+    return out, float(ms.value)
+
+
+def itq3s_matmul(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None, _timed=None):
     """Y[M, N] = X[M, K] @ W_hat[N, K]^T from the packed weights.  X: float16 device tensor."""
     _need_cuda(codes, scales, X, out, workspace, status_flags)
     if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
@@ -143,10 +153,12 @@ def itq3s_matmul(codes, scales, N, K, X, out=None, dtype=torch.float32, workspac
     need = itq3s_matmul_workspace_bytes(M, N, K)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
-    _check(
-        lib().itq3s_matmul(
-            _ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
-            out.stride(0), _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(status_flags), _stream(),
-        )
+    args = (
+        _ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
+        out.stride(0), _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(status_flags), _stream(),
     )
+    if _timed is None:
+        _check(lib().itq3s_matmul(*args))
+    else:
+        _check(lib().itq3s_matmul_timed(*args, ctypes.byref(_timed)))
     return out

@@ -98,6 +98,27 @@ int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64
     return itq3s::launch_gemm(codes, scales, N, K, Xt, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
 }
 
+int itq3s_matmul_timed(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
+                       void* Y, int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream,
+                       float* kernel_ms) {
+    if (!kernel_ms) return ITQ3S_ERR_NULL;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return ITQ3S_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return ITQ3S_ERR_LAUNCH;
+    }
+    itq3s::set_launch_timing(e0, e1);
+    int rc = itq3s_matmul(codes, scales, N, K, X, M, ldx, Y, y_dtype, ldy, workspace, workspace_bytes, status_flags, stream);
+    (void)itq3s::take_launch_timing();  // disarm if validation returned before any launch
+    if (rc == ITQ3S_OK) {
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(kernel_ms, e0, e1) != hipSuccess) rc = ITQ3S_ERR_LAUNCH;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
 const char* itq3s_strerror(int status) {
     switch (status) {
         case ITQ3S_OK: return "ok";

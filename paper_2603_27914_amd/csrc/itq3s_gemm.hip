@@ -12,6 +12,8 @@
 // Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 (m) x 128 (n) x 64 (k), wavefront tile 64 x 64
 // as 2 x 2 v_mfma_f32_32x32x16_f16.  A operand = x~ rows, B operand = weight rows, so a lane's
 // accumulator column is an output channel n and stores are contiguous along n.
+#include <hip/hip_ext.h>
+
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
@@ -155,7 +157,9 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
     a.codes = codes; a.scales = scales; a.Xt = Xt; a.Y = Y; a.flags = flags;
     a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
     dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-    hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, a);
+    const LaunchTiming tm = take_launch_timing();
+    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, tm.start, tm.stop, 0, a);
+    else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -26,6 +26,8 @@
 // unrolled D+1 times so that ring indices are static).  Every load in the pipeline is issued
 // unconditionally -- steps past the end of a wavefront's list re-read tile 0, which is cached -- so
 // that the load counter alone, not a full drain, orders loads and use.
+#include <hip/hip_ext.h>
+
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
@@ -35,6 +37,14 @@ constexpr int kGemvWaves = 8;        // wavefronts per workgroup
 constexpr int kGemvMaxRT = 7;        // row tiles per workgroup, at most
 constexpr int kFusedMaxBlocks = 4;   // fused rotation: blocks per wavefront times MP, at most (more costs
                                      // more than the separate rotation launch it saves)
+
+static LaunchTiming g_timing;
+void set_launch_timing(hipEvent_t start, hipEvent_t stop) { g_timing.start = start; g_timing.stop = stop; }
+LaunchTiming take_launch_timing() {
+    const LaunchTiming t = g_timing;
+    g_timing = LaunchTiming{};
+    return t;
+}
 
 struct GemvArgs {
     const uint32_t* codes;
@@ -307,7 +317,9 @@ static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
         lds_limit_raised = true;
     }
     const size_t lds = (kFused ? (size_t)kGemvWaves * (kFusedMaxBlocks / MP) * MP * (512 + 4) : 0) + (size_t)kGemvWaves * RT * MP * 16 * 4;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
+    const LaunchTiming tm = take_launch_timing();
+    if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
+    else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -12,6 +12,16 @@ constexpr uint32_t kFlagNonFinite = 1u, kFlagScaleSat = 2u, kFlagZClamp = 4u, kF
 // Streaming path handles up to this many activation rows; more rows go to the tiled MFMA path.
 constexpr int kGemvMaxM = 16;
 
+// Optional device-side timing of the contraction kernel.  set_launch_timing() arms a pair of events;
+// the next launch of a contraction kernel (streaming or tiled) takes them (take_launch_timing clears
+// the pair) and attaches them to its own dispatch, so that their distance is the kernel's duration
+// by the GPU's timestamps, without launch gaps.  Not thread-safe: a measurement aid.
+struct LaunchTiming {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+void set_launch_timing(hipEvent_t start, hipEvent_t stop);
+LaunchTiming take_launch_timing();
+
 int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* flags,
                     hipStream_t stream);
 

@@ -266,6 +266,22 @@ def test_matmul_is_deterministic(gpu, ref):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (4, 1000, 11008), (16, 2048, 2048), (64, 512, 1024)])
+def test_matmul_timed_variant_same_result_and_positive_time(gpu, ref, M, N, K):
+    """The measurement entry point runs the same kernels: identical output, a plausible duration,
+    and a plain call afterwards is unaffected (the armed events are consumed)."""
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "timed")
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    X = to_dev(torch, synth.activations(M, K, "timed"))
+    want = binding.itq3s_matmul(cd, sd, N, K, X).cpu().numpy()
+    got, ms = binding.itq3s_matmul_timed(cd, sd, N, K, X)
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert 0.0 < ms < 50.0
+    again = binding.itq3s_matmul(cd, sd, N, K, X).cpu().numpy()
+    assert np.array_equal(again, want)
+
+
 def test_matmul_flags_high_plane(gpu, ref):
     torch, binding = gpu
     codes, scales = synth.random_packed(64, 512, "hp")
