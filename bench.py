@@ -33,7 +33,12 @@ MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 # HBM traffic of the streaming kernel per launch, averaged over the step's launches, from two
 # rocprofv3 --pmc passes over this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
 # counter shows for copy_leg's 1 GiB copy; the summaries and the commands are under profiles/.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # (128 x 6608.9 + 64 x 17456.4 + 32 x 17551.9) / 224 KiB fetched, (128 x 16 + 64 x 43 + 32 x 16) / 224 KiB
+    # written, against 11,327,707 algorithmic bytes: 2 % of re-reads (activations and stand-in loads)
+    "llama7b_decode": {"bytes_per_launch": 11566270, "fetch_bytes": 11541987, "write_bytes": 24283,
+                       "source": "profiles/gemv_llama7b_decode.hbm_traffic.txt"},
+}
 
 WORKLOADS = {
     # name: (layers, [(tensor, N, K, copies)], M)
@@ -173,7 +178,7 @@ def main():
         med = v[len(v) // 2]
         per_kernel.append({"N": N, "K": K, "launches": len(v), "us_mean": round(1e3 * sum(v) / len(v), 3), "us_median": round(1e3 * med, 3),
                            "us_min": round(1e3 * v[0], 3), "GBps_mean": round(alg_bytes(N, K, M) / (sum(v) / len(v) * 1e-3) / 1e9, 1)})
-    traffic = MEASURED_TRAFFIC.get(args.workload) if layers == WORKLOADS[args.workload][0] else None
+    measured = MEASURED_TRAFFIC.get(args.workload) if layers == WORKLOADS[args.workload][0] else None
 
     out = {
         "metric": "ITQ3_S GEMV effective HBM GB/s on packed-weight bytes @M=1",
@@ -200,7 +205,8 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": traffic,
+            "traffic": measured["bytes_per_launch"] if measured else None,
+            "traffic_detail": measured,
             "avg_launch_us": round(avg_launch_ms * 1e3, 3),
             "alg_bytes_per_launch": int(step_alg / calls),
             "launches_timed": len(all_ms),

@@ -1,0 +1,64 @@
+"""Condense rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+  python -m paper_2603_27914_amd.profsum stats <..._kernel_stats.csv>
+      rows of `rocprofv3 --kernel-trace --stats --output-format csv` for this library's kernels
+      (and the runtime's copy kernel): calls, average / min / max duration.
+
+  python -m paper_2603_27914_amd.profsum pmc <..._counter_collection.csv> --copy-kib 1048576
+      per kernel and launch shape, the mean of the collected counter (FETCH_SIZE or WRITE_SIZE, KiB
+      per dispatch), the calibration factor (known KiB of bench.py's plain 1 GiB copy / what the same
+      counter shows for it) and the scaled value.
+"""
+import argparse
+import collections
+import csv
+import re
+
+
+def short(name):
+    name = re.sub(r"\(.*$", "", name)
+    return name.replace("void ", "").replace("itq3s::", "")
+
+
+def ours(name):
+    return "itq3s" in name or "copyBuffer" in name
+
+
+def stats(path):
+    print("%-44s %7s %12s %10s %10s" % ("kernel", "calls", "avg_ns", "min_ns", "max_ns"))
+    for r in csv.DictReader(open(path)):
+        if ours(r["Name"]):
+            print("%-44s %7d %12.1f %10d %10d" % (short(r["Name"])[:44], int(r["Calls"]), float(r["AverageNs"]), int(r["MinNs"]), int(r["MaxNs"])))
+
+
+def pmc(path, copy_kib):
+    agg = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        if ours(r["Kernel_Name"]):
+            agg[(short(r["Kernel_Name"]), int(r["Grid_Size"]), r["Counter_Name"])].append(float(r["Counter_Value"]))
+    big = [(sum(v) / len(v), k) for k, v in agg.items() if "copyBuffer" in k[0]]
+    factor = None
+    if big and copy_kib:
+        measured = max(big)[0]
+        factor = copy_kib / measured if measured > 0 else None
+    print("calibration: plain copy of %s KiB shows %s -> factor %s" % (copy_kib, ("%.1f" % max(big)[0]) if big else "n/a", ("%.4f" % factor) if factor else "n/a"))
+    print("%-36s %9s %-11s %7s %14s %14s" % ("kernel", "threads", "counter", "calls", "mean_KiB", "scaled_KiB"))
+    for (name, grid, ctr), v in sorted(agg.items()):
+        mean = sum(v) / len(v)
+        print("%-36s %9d %-11s %7d %14.1f %14s" % (name[:36], grid, ctr, len(v), mean, ("%.1f" % (mean * factor)) if factor else "n/a"))
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("mode", choices=["stats", "pmc"])
+    ap.add_argument("csv")
+    ap.add_argument("--copy-kib", type=float, default=0.0, help="known KiB the calibration copy reads (= writes)")
+    a = ap.parse_args()
+    if a.mode == "stats":
+        stats(a.csv)
+    else:
+        pmc(a.csv, a.copy_kib)
+
+
+if __name__ == "__main__":
+    main()
