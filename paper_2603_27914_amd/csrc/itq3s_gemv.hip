@@ -18,8 +18,9 @@
 // a workgroup, wavefront w takes blocks b = w, w+W, ...; no two wavefronts share a block, so each
 // prepares the x~ fragments of its own blocks by itself and the only barrier is the one before the
 // final cross-wavefront sum.  Two ways to get the fragments:
-//   kFused : the wavefront rotates its blocks of X itself (256-point butterflies across the 64 lanes)
-//            and parks the result in its private slice of LDS -- one launch per matmul;
+//   kFused : the wavefront rotates its blocks of X itself (two small products on the matrix cores,
+//            see HadamardOperand) and parks the result in its private slice of LDS -- one launch
+//            per matmul;
 //   direct : a separate rotation kernel has written x~ in operand order to the workspace and the
 //            fragments are loaded from there next to the tiles (larger M or K).
 // Tile loads run D blocks ahead of the arithmetic through a ring of D+1 register buffers (loop
@@ -35,8 +36,8 @@ namespace itq3s {
 
 constexpr int kGemvWaves = 8;        // wavefronts per workgroup
 constexpr int kGemvMaxRT = 7;        // row tiles per workgroup, at most
-constexpr int kFusedMaxBlocks = 4;   // fused rotation: blocks per wavefront times MP, at most (more costs
-                                     // more than the separate rotation launch it saves)
+constexpr int kFusedMaxBlocks = 16;  // fused rotation: blocks per wavefront times MP, at most (bounds the
+                                     // registers and the LDS the rotated activations take)
 
 static LaunchTiming g_timing;
 void set_launch_timing(hipEvent_t start, hipEvent_t stop) { g_timing.start = start; g_timing.stop = stop; }
@@ -55,6 +56,7 @@ struct GemvArgs {
     uint32_t* flags;
     int64_t N, ldx, ldy;
     int NT, KB, M, y_f16;
+    int nt_q, nt_r;  // row tiles per workgroup: the first nt_r workgroups own nt_q + 1, the others nt_q
 };
 
 struct TileRegs {
@@ -112,68 +114,81 @@ __device__ __forceinline__ float lane_xor(float v) {
     return __builtin_bit_cast(float, x);
 }
 
-template <int MASK>
-__device__ __forceinline__ void butterfly_stage(float (&v)[4], int lane) {
-    const bool upper = (lane & MASK) != 0;
+// The 256-point transform on the matrix cores.  With the chunk written as a 16 x 16 matrix
+// X[a][b] = x[16a + b], the Sylvester construction gives H_256 = H_16 (x) H_16, i.e.
+//     (H x)[16a' + b'] = (H_16 X H_16)[a'][b'] / 16        (H_16 with entries +-1).
+// Two 16x16x16 products do it: T = X (H_16/4) (fp16 inputs, exact products, fp32 sums; the factor
+// keeps |T| <= 4 max|x| inside the fp16 range), then H_16 T with T split into two halves
+// (T = T_hi + T_lo keeps 22 bits), then the remaining factor 1/4.  The accumulator layout of the
+// first product (lane = column b', four rows a per lane) is exactly the B-operand layout of the
+// second, so nothing moves between lanes.  A lane holds x[16 (l%16) + 4 (l/16) + 0..3] on entry and
+// element e = 64 (l/16) + 16 r + l%16, r = 0..3, of the result.
+struct HadamardOperand {
+    half4 h, q;  // H_16[4g + j][r16] and a quarter of it, j = 0..3: B operand of the first product, A operand of the second
+    __device__ __forceinline__ void init(int lane) {
+        const int r16 = lane & 15, g = lane >> 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float p = lane_xor<MASK>(v[i]);
-        v[i] = upper ? (p - v[i]) : (v[i] + p);
+        for (int j = 0; j < 4; ++j) {
+            const bool neg = (__builtin_popcount((4 * g + j) & r16) & 1) != 0;
+            h[j] = neg ? (_Float16)(-1.0f) : (_Float16)1.0f;
+            q[j] = neg ? (_Float16)(-0.25f) : (_Float16)0.25f;
+        }
     }
-}
+};
 
-// x~ = H x for one 256-chunk held as elements 4l..4l+3 per lane, rounded to fp16, scattered into
-// operand order at `dst` (256*MP halves: index ((t*4 + g)*MP + m)*8 + i); returns sum of the rounded
-// values in every lane.
+// x~ = H x for one 256-chunk, rounded to fp16, scattered into operand order at `dst` (256*MP halves:
+// index ((t*4 + g)*MP + m)*8 + i); returns the sum of the rounded values in every lane.
 template <int MP>
-__device__ __forceinline__ float rotate_to_lds(u32x2 raw, int lane, int m, _Float16* dst) {
-    const half4 h = __builtin_bit_cast(half4, raw);
-    float v[4] = {(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
-    const float t0 = v[0] + v[1], t1 = v[0] - v[1], t2 = v[2] + v[3], t3 = v[2] - v[3];
-    v[0] = t0 + t2; v[2] = t0 - t2; v[1] = t1 + t3; v[3] = t1 - t3;
-    butterfly_stage<1>(v, lane);
-    butterfly_stage<2>(v, lane);
-    butterfly_stage<4>(v, lane);
-    butterfly_stage<8>(v, lane);
-    butterfly_stage<16>(v, lane);
-    butterfly_stage<32>(v, lane);
+__device__ __forceinline__ float rotate_to_lds(u32x2 raw, const HadamardOperand& H, int lane, int m, _Float16* dst) {
+    const half4 xa = __builtin_bit_cast(half4, raw);
+    const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+    const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(xa, H.q, zero, 0, 0, 0);
+    half4 th, tl;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        th[j] = (_Float16)T[j];
+        tl[j] = (_Float16)(T[j] - (float)th[j]);
+    }
+    floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(H.h, th, zero, 0, 0, 0);
+    U = __builtin_amdgcn_mfma_f32_16x16x16f16(H.h, tl, U, 0, 0, 0);
     _Float16 r[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = (_Float16)(v[i] * 0.0625f);
+    for (int i = 0; i < 4; ++i) r[i] = (_Float16)(U[i] * 0.25f);
     float s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
     s += lane_xor<1>(s); s += lane_xor<2>(s); s += lane_xor<4>(s); s += lane_xor<8>(s); s += lane_xor<16>(s); s += lane_xor<32>(s);
-    // element e = 4l + j: quarter g = e>>6, word w = (e>>4)&3, slot = e&15 = 4q + j with q = l&3;
-    // MFMA step t = 2w + ((slot&7)>>2) = 2w + (q&1), position i = 2(slot&3) + (slot>>3) = 2j + (q>>1)
-    const int g = lane >> 4, w = (lane >> 2) & 3, q = lane & 3;
-    const int t = 2 * w + (q & 1), i0 = q >> 1;
-    _Float16* p = dst + ((t * 4 + g) * MP + m) * 8 + i0;
+    // element e = 64g + 16w + slot (w = r, slot = l%16): quarter g, low-plane word w, code slot `slot`;
+    // MFMA step t = 2w + ((slot&7)>>2), position i = 2(slot&3) + (slot>>3)
+    const int g = lane >> 4, slot = lane & 15;
+    const int tb = (slot & 7) >> 2, i0 = 2 * (slot & 3) + (slot >> 3);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) p[2 * j] = r[j];
+    for (int w = 0; w < 4; ++w) dst[(((2 * w + tb) * 4 + g) * MP + m) * 8 + i0] = r[w];
     return s;
 }
 
-template <int MP, int RT, int D, bool kFused>
+// NBX = 0: direct; NBX > 0: fused, with room for NBX blocks per wavefront (NBX * MP <= kFusedMaxBlocks).
+template <int MP, int RT, int D, int NBX>
 __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a) {
+    constexpr bool kFused = NBX > 0;
     constexpr int W = kGemvWaves;
     constexpr int NB = D + 1;
-    constexpr int NBX = kFusedMaxBlocks / MP;  // kFused: blocks per wavefront, at most
     extern __shared__ __align__(16) unsigned char smem[];
     const int KB = a.KB;
 
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // wave-uniform, in an SGPR
     const int g = lane >> 4, r16 = lane & 15, mm = r16 & (MP - 1);
-    const int nt_begin = (int)(((int64_t)blockIdx.x * a.NT) / gridDim.x);
-    const int nt_end = (int)(((int64_t)(blockIdx.x + 1) * a.NT) / gridDim.x);
-    const int cnt = nt_end - nt_begin;  // RT-1 or RT row tiles (the host picks the grid that way)
+    // RT-1 or RT row tiles (the host picks the grid that way); no division on the way to the first load
+    const int wg = (int)blockIdx.x;
+    const int nt_begin = wg * a.nt_q + (wg < a.nt_r ? wg : a.nt_r);
+    const int cnt = a.nt_q + (wg < a.nt_r ? 1 : 0);
     const bool full = RT == 1 || cnt == RT;
     const int nb = KB > wave ? (KB - wave + W - 1) / W : 0;  // blocks of this wavefront: b = wave + j*W
 
     // LDS: kFused: per wavefront NBX*MP*256 halves of x~, then NBX*MP sums per wavefront; then the
     // reduction buffer
-    _Float16* xs = reinterpret_cast<_Float16*>(smem) + (size_t)wave * (kFused ? NBX * MP * 256 : 0);
-    float* ss = reinterpret_cast<float*>(smem + (kFused ? (size_t)W * NBX * MP * 512 : 0)) + wave * NBX * MP;
-    float* red = reinterpret_cast<float*>(smem + (kFused ? (size_t)W * NBX * MP * (512 + 4) : 0));  // W*RT*MP*16 floats
+    _Float16* xs = reinterpret_cast<_Float16*>(smem) + (size_t)wave * NBX * MP * 256;
+    float* ss = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * 512) + wave * NBX * MP;
+    float* red = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * (512 + 4));  // W*RT*MP*16 floats
 
     floatx4 acc[RT];
 #pragma unroll
@@ -239,6 +254,9 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     };
 
     // ---- activations of this wavefront's blocks first (kFused), then the first D steps of tiles
+    // (straight-line like the tile pipeline: slots past the wavefront's list re-read block 0 and are
+    // rotated like the others; the host picks the smallest NBX that holds the list, because a load
+    // costs address-unit time even when it hits)
     u32x2 xraw[kFused ? NBX * MP : 1];
     if constexpr (kFused) {
 #pragma unroll
@@ -247,23 +265,23 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
 #pragma unroll
             for (int m = 0; m < MP; ++m) {
                 const int mr = m < a.M ? m : 0;
-                xraw[j * MP + m] = *reinterpret_cast<const u32x2*>(a.X + (size_t)mr * a.ldx + (size_t)b * kBlock + 4 * lane);
+                xraw[j * MP + m] = *reinterpret_cast<const u32x2*>(a.X + (size_t)mr * a.ldx + (size_t)b * kBlock + 16 * r16 + 4 * g);
             }
         }
     }
 #pragma unroll
     for (int d = 0; d < D; ++d) issue(ring[d], d);
     if constexpr (kFused) {
+        HadamardOperand H;
+        H.init(lane);
 #pragma unroll
         for (int j = 0; j < NBX; ++j) {
-            if (j < nb) {
 #pragma unroll
-                for (int m = 0; m < MP; ++m) {
-                    u32x2 raw = xraw[j * MP + m];
-                    if (m >= a.M) raw = u32x2{0u, 0u};
-                    const float s = rotate_to_lds<MP>(raw, lane, m, xs + (size_t)j * MP * 256);
-                    if (lane == 0) ss[j * MP + m] = s;
-                }
+            for (int m = 0; m < MP; ++m) {
+                u32x2 raw = xraw[j * MP + m];
+                if (m >= a.M) raw = u32x2{0u, 0u};
+                const float s = rotate_to_lds<MP>(raw, H, lane, m, xs + (size_t)j * MP * 256);
+                if (lane == 0) ss[j * MP + m] = s;
             }
         }
     }
@@ -308,15 +326,15 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
-template <int MP, int RT, int D, bool kFused>
+template <int MP, int RT, int D, int NBX>
 static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
-    auto kern = gemv_kernel<MP, RT, D, kFused>;
+    auto kern = gemv_kernel<MP, RT, D, NBX>;
     static bool lds_limit_raised = false;  // once per instantiation: allow up to the 160 KB of a CU
     if (!lds_limit_raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
         lds_limit_raised = true;
     }
-    const size_t lds = (kFused ? (size_t)kGemvWaves * (kFusedMaxBlocks / MP) * MP * (512 + 4) : 0) + (size_t)kGemvWaves * RT * MP * 16 * 4;
+    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 4) + (size_t)kGemvWaves * RT * MP * 16 * 4;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
@@ -333,37 +351,59 @@ static int cu_count() {
     return n;
 }
 
-// Row tiles per workgroup and prefetch depth: about 8 tiles in flight per wavefront, but never deeper
-// than the shortest wavefront's list of blocks (deeper would only add stand-in loads), and shallow
-// enough that the ring fits the register file (the direct path keeps the x~ fragments in the ring too).
+// Prefetch depth the register file allows for RT row tiles per workgroup (the direct path keeps the
+// x~ fragments in the ring too, MP = 4 rotates four rows per block).
 template <int MP, bool kFused>
-static int launch_shape(const GemvArgs& a, int grid, int rt, int nb_min, hipStream_t stream) {
-    const int dmax = nb_min < 1 ? 1 : nb_min;
+constexpr int max_depth(int rt) {
+    if (kFused) return rt <= 2 ? 4 : (rt == 3 || (rt == 4 && MP <= 2)) ? 2 : 1;
+    return rt == 1 ? 4 : rt <= 3 ? 2 : 1;
+}
+
+// Smallest of 2, 4, 8, 16 that holds nb_max blocks per wavefront (fused path); 0 = direct.
+template <int MP, int RT, int D, bool kFused>
+static int launch_nbx(const GemvArgs& a, int grid, int nb_max, hipStream_t stream) {
+    if constexpr (D > max_depth<MP, kFused>(RT)) {
+        return -6;
+    } else if constexpr (!kFused) {
+        return launch_one<MP, RT, D, 0>(a, grid, stream);
+    } else {
+        // D <= blocks of the least busy wavefront <= nb_max <= NBX: deeper combinations cannot occur
+        if (nb_max <= 2) {
+            if constexpr (D <= 2) return launch_one<MP, RT, D, 2>(a, grid, stream);
+        } else if (nb_max <= 4) {
+            if constexpr (4 * MP <= kFusedMaxBlocks && D <= 4) return launch_one<MP, RT, D, 4>(a, grid, stream);
+        } else if (nb_max <= 8) {
+            if constexpr (8 * MP <= kFusedMaxBlocks && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 8>(a, grid, stream);
+        } else {
+            if constexpr (16 * MP <= kFusedMaxBlocks && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 16>(a, grid, stream);
+        }
+        return -6;
+    }
+}
+
+template <int MP, int RT, bool kFused>
+static int launch_depth(const GemvArgs& a, int grid, int nb_min, int nb_max, hipStream_t stream) {
+    // about 8 tiles in flight per wavefront, never deeper than the shortest wavefront's list of blocks
+    // (deeper would only add stand-in loads)
+    int d = max_depth<MP, kFused>(RT);
+    while (d > 1 && d > nb_min) d >>= 1;
+    switch (d) {
+        case 4: return launch_nbx<MP, RT, 4, kFused>(a, grid, nb_max, stream);
+        case 2: return launch_nbx<MP, RT, 2, kFused>(a, grid, nb_max, stream);
+        default: return launch_nbx<MP, RT, 1, kFused>(a, grid, nb_max, stream);
+    }
+}
+
+template <int MP, bool kFused>
+static int launch_shape(const GemvArgs& a, int grid, int rt, int nb_min, int nb_max, hipStream_t stream) {
     switch (rt) {
-        case 1:
-            if constexpr (kFused) {
-                if (dmax >= 8) return launch_one<MP, 1, 8, kFused>(a, grid, stream);
-            }
-            if (dmax >= 4) return launch_one<MP, 1, 4, kFused>(a, grid, stream);
-            if (dmax >= 2) return launch_one<MP, 1, 2, kFused>(a, grid, stream);
-            return launch_one<MP, 1, 1, kFused>(a, grid, stream);
-        case 2:
-            if constexpr (kFused) {
-                if (dmax >= 4) return launch_one<MP, 2, 4, kFused>(a, grid, stream);
-            }
-            if (dmax >= 2) return launch_one<MP, 2, 2, kFused>(a, grid, stream);
-            return launch_one<MP, 2, 1, kFused>(a, grid, stream);
-        case 3:
-            if (dmax >= 2) return launch_one<MP, 3, 2, kFused>(a, grid, stream);
-            return launch_one<MP, 3, 1, kFused>(a, grid, stream);
-        case 4:
-            if constexpr (kFused && MP <= 2) {
-                if (dmax >= 2) return launch_one<MP, 4, 2, kFused>(a, grid, stream);
-            }
-            return launch_one<MP, 4, 1, kFused>(a, grid, stream);
-        case 5: return launch_one<MP, 5, 1, kFused>(a, grid, stream);
-        case 6: return launch_one<MP, 6, 1, kFused>(a, grid, stream);
-        default: return launch_one<MP, 7, 1, kFused>(a, grid, stream);
+        case 1: return launch_depth<MP, 1, kFused>(a, grid, nb_min, nb_max, stream);
+        case 2: return launch_depth<MP, 2, kFused>(a, grid, nb_min, nb_max, stream);
+        case 3: return launch_depth<MP, 3, kFused>(a, grid, nb_min, nb_max, stream);
+        case 4: return launch_depth<MP, 4, kFused>(a, grid, nb_min, nb_max, stream);
+        case 5: return launch_depth<MP, 5, kFused>(a, grid, nb_min, nb_max, stream);
+        case 6: return launch_depth<MP, 6, kFused>(a, grid, nb_min, nb_max, stream);
+        default: return launch_depth<MP, 7, kFused>(a, grid, nb_min, nb_max, stream);
     }
 }
 
@@ -384,21 +424,23 @@ int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
     int grid = a.NT < cu_count() ? a.NT : cu_count();
     if ((a.NT + grid - 1) / grid > max_rt) grid = (a.NT + max_rt - 1) / max_rt;
     const int rt = (a.NT + grid - 1) / grid;  // every workgroup gets rt or rt-1 row tiles
-    const int nb_min = a.KB / kGemvWaves;
+    a.nt_q = a.NT / grid;
+    a.nt_r = a.NT % grid;
+    const int nb_min = a.KB / kGemvWaves, nb_max = (a.KB + kGemvWaves - 1) / kGemvWaves;
     if (fused) {
         switch (MP) {
-            case 1: return launch_shape<1, true>(a, grid, rt, nb_min, stream);
-            case 2: return launch_shape<2, true>(a, grid, rt, nb_min, stream);
-            case 4: return launch_shape<4, true>(a, grid, rt, nb_min, stream);
+            case 1: return launch_shape<1, true>(a, grid, rt, nb_min, nb_max, stream);
+            case 2: return launch_shape<2, true>(a, grid, rt, nb_min, nb_max, stream);
+            case 4: return launch_shape<4, true>(a, grid, rt, nb_min, nb_max, stream);
         }
         return -2;
     }
     switch (MP) {
-        case 1: return launch_shape<1, false>(a, grid, rt, nb_min, stream);
-        case 2: return launch_shape<2, false>(a, grid, rt, nb_min, stream);
-        case 4: return launch_shape<4, false>(a, grid, rt, nb_min, stream);
-        case 8: return launch_shape<8, false>(a, grid, rt, nb_min, stream);
-        case 16: return launch_shape<16, false>(a, grid, rt, nb_min, stream);
+        case 1: return launch_shape<1, false>(a, grid, rt, nb_min, nb_max, stream);
+        case 2: return launch_shape<2, false>(a, grid, rt, nb_min, nb_max, stream);
+        case 4: return launch_shape<4, false>(a, grid, rt, nb_min, nb_max, stream);
+        case 8: return launch_shape<8, false>(a, grid, rt, nb_min, nb_max, stream);
+        case 16: return launch_shape<16, false>(a, grid, rt, nb_min, nb_max, stream);
     }
     return -2;
 }
