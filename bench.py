@@ -41,9 +41,9 @@ MEASURED_TRAFFIC = {
 }
 
 WORKLOADS = {
-    # name: (layers, [(tensor, N, K, copies)], M)
-    "llama7b_decode": (32, "LLAMA7B_LAYER", 1),
-    "llama70b_decode": (80, "LLAMA70B_LAYER", 1),
+    # name: (layers, stages of one layer in paper_2603_27914_amd.synth, M)
+    "llama7b_decode": (32, "LLAMA7B_STAGES", 1),
+    "llama70b_decode": (80, "LLAMA70B_STAGES", 1),
 }
 
 
@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
+    ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
     ap.add_argument("--legs", default="per_shape,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -101,20 +102,20 @@ def main():
     gen = torch.Generator(device="cuda")
     gen.manual_seed(synth.MASTER_SEED)
 
-    layers, layer_name, M = WORKLOADS[args.workload]
+    layers, stages_name, M = WORKLOADS[args.workload]
     if args.layers > 0:
         layers = args.layers
-    layer = getattr(synth, layer_name)
+    stages = getattr(synth, stages_name)
+    grouped = not args.ungrouped
 
     # ------------------------------------------------------------------ build the resident weights
     flags = torch.zeros(1, dtype=torch.int32, device="cuda")
-    tensors = []  # (N, K, codes, scales, layer index, tensor index)
+    tensors = []  # (N, K, codes, scales, layer index, stage index, name)
     q_ms, q_bytes = 0.0, 0
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_build = time.time()
     for li in range(layers):
-        for ti, (name, N, K, copies) in enumerate(layer):
-            for c in range(copies):
+        for si, stage in enumerate(stages):
+            for name, N, K in stage:
                 W = student_t_weights(torch, gen, N, K)
                 codes, scales = binding.alloc_packed(N, K)
                 ev0.record()
@@ -123,24 +124,35 @@ def main():
                 ev1.synchronize()
                 q_ms += ev0.elapsed_time(ev1)
                 q_bytes += N * K * 4 + packed_bytes(N, K)
-                tensors.append((N, K, codes, scales, li, ti))
+                tensors.append((N, K, codes, scales, li, si, name))
                 del W
     assert int(flags.item()) == 0, "quantizer raised data flags on synthetic weights"
-    t_build = time.time() - t_build
     xs = {}
-    for name, N, K, copies in layer:
+    for stage in stages:
+        K = stage[0][2]
         if K not in xs:
             xs[K] = activations(torch, gen, M, K)
-    ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for _, N, K, _ in layer}
-    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for _, N, K, _ in layer), dtype=torch.uint8, device="cuda")
+    ys = {name: torch.empty((M, N), dtype=torch.float32, device="cuda") for stage in stages for name, N, K in stage}
+    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for stage in stages for _, N, K in stage), dtype=torch.uint8, device="cuda")
+
+    # the library calls of a step, in order: one per stage of every layer (the tensors of a stage read
+    # the same activations: one grouped call), or one per tensor with --ungrouped
+    calls = []  # (K, [(codes, scales, N)], [Y])
+    for li in range(layers):
+        for si in range(len(stages)):
+            group = [t for t in tensors if t[4] == li and t[5] == si]
+            if grouped:
+                calls.append((group[0][1], [(c, s, N) for N, K, c, s, *_ in group], [ys[t[6]] for t in group]))
+            else:
+                calls.extend((K, [(c, s, N)], [ys[name]]) for N, K, c, s, _, _, name in group)
 
     def step():
-        for N, K, codes, scales, li, ti in tensors:
-            binding.itq3s_matmul(codes, scales, N, K, xs[K], out=ys[N], workspace=ws, status_flags=None)
+        for K, wts, outs in calls:
+            binding.itq3s_matmul_grouped(wts, K, xs[K], outs=outs, workspace=ws)
 
     # ------------------------------------------------------------------ timed region
     # The step is captured once into a HIP graph and replayed, so that the timed region measures
-    # the GPU and not the Python interpreter issuing several hundred launches.
+    # the GPU and not the Python interpreter issuing the launches.
     step()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -161,24 +173,23 @@ def main():
     step_packed = sum(packed_bytes(N, K) for N, K, *_ in tensors)
     step_alg = sum(alg_bytes(N, K, M) for N, K, *_ in tensors)
     value = step_packed / (ms_per_step * 1e-3) / 1e9
-    calls = len(tensors)
     # dominant kernel = the streaming contraction (gemv_kernel), one launch per call: its duration by
-    # the events attached to each dispatch, one pass over the step's tensors in step order (every
-    # tensor comes from HBM: 2.5 GB lie between two uses of the same one)
+    # the events attached to each dispatch, one pass over the step's calls in step order (every
+    # tensor comes from HBM: the whole stack lies between two uses of the same one)
     kern_ms = {}
-    for N, K, codes, scales, li, ti in tensors:
-        _, ms = binding.itq3s_matmul_timed(codes, scales, N, K, xs[K], out=ys[N], workspace=ws)
-        kern_ms.setdefault((N, K), []).append(ms)
+    for K, wts, outs in calls:
+        _, ms = binding.itq3s_matmul_grouped_timed(wts, K, xs[K], outs=outs, workspace=ws)
+        kern_ms.setdefault((K, tuple(N for _, _, N in wts)), []).append(ms)
     all_ms = [m for v in kern_ms.values() for m in v]
     avg_launch_ms = sum(all_ms) / len(all_ms)
-    achieved = (step_alg / calls) / (avg_launch_ms * 1e-3) / 1e9
+    achieved = (step_alg / len(calls)) / (avg_launch_ms * 1e-3) / 1e9
     per_kernel = []
-    for (N, K), v in kern_ms.items():
+    for (K, Ns), v in kern_ms.items():
         v = sorted(v)
-        med = v[len(v) // 2]
-        per_kernel.append({"N": N, "K": K, "launches": len(v), "us_mean": round(1e3 * sum(v) / len(v), 3), "us_median": round(1e3 * med, 3),
-                           "us_min": round(1e3 * v[0], 3), "GBps_mean": round(alg_bytes(N, K, M) / (sum(v) / len(v) * 1e-3) / 1e9, 1)})
-    measured = MEASURED_TRAFFIC.get(args.workload) if layers == WORKLOADS[args.workload][0] else None
+        nbytes = sum(alg_bytes(N, K, M) for N in Ns)
+        per_kernel.append({"K": K, "N": list(Ns), "launches": len(v), "us_mean": round(1e3 * sum(v) / len(v), 3), "us_median": round(1e3 * v[len(v) // 2], 3),
+                           "us_min": round(1e3 * v[0], 3), "alg_bytes": nbytes, "GBps_mean": round(nbytes / (sum(v) / len(v) * 1e-3) / 1e9, 1)})
+    measured = MEASURED_TRAFFIC.get(args.workload) if layers == WORKLOADS[args.workload][0] and grouped else None
 
     out = {
         "metric": "ITQ3_S GEMV effective HBM GB/s on packed-weight bytes @M=1",
@@ -194,13 +205,14 @@ def main():
         "dtype": "f16",
         "data": "synthetic",
         "config": {
-            "workload": "%s: %d layers x %s, M=%d, %d matmul calls, %.2f GB packed resident in HBM"
-            % (args.workload, layers, "+".join("%dx(%dx%d)" % (c, N, K) for _, N, K, c in layer), M, calls, step_packed / 1e9),
+            "workload": "%s: %d layers x [%s], M=%d, %d tensors in %d library calls (%s), %.2f GB packed resident in HBM"
+            % (args.workload, layers, " -> ".join("+".join("%s %dx%d" % t for t in st) for st in stages), M, len(tensors), len(calls),
+               "tensors that read the same activations share a launch" if grouped else "one call per tensor", step_packed / 1e9),
             "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "gemv_kernel (itq3s_matmul, M<=16 path)",
+            "kernel": "gemv_kernel (itq3s_matmul / itq3s_matmul_grouped, M<=16 path)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
@@ -208,17 +220,17 @@ def main():
             "traffic": measured["bytes_per_launch"] if measured else None,
             "traffic_detail": measured,
             "avg_launch_us": round(avg_launch_ms * 1e3, 3),
-            "alg_bytes_per_launch": int(step_alg / calls),
+            "alg_bytes_per_launch": int(step_alg / len(calls)),
             "launches_timed": len(all_ms),
             "per_kernel": per_kernel,
-            "step_wall_us_per_call": round(ev_ms / (args.steps * calls) * 1e3, 3),
+            "step_wall_us_per_call": round(ev_ms / (args.steps * len(calls)) * 1e3, 3),
         },
         "quantize": {"GBps": round(q_bytes / (q_ms * 1e-3) / 1e9, 1), "bytes": q_bytes, "ms": round(q_ms, 2), "frac_of_hbm_peak": round(q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
     }
 
     legs = [] if args.no_extras else [x for x in args.legs.split(",") if x]
     if "per_shape" in legs:
-        out["per_shape"] = per_shape_leg(torch, binding, tensors, layer, gen)
+        out["per_shape"] = per_shape_leg(torch, binding, tensors, gen)
     if "prefill" in legs:
         out["prefill"] = prefill_leg(torch, binding, synth, gen)
     if "dequantize" in legs:
@@ -226,7 +238,7 @@ def main():
     if "copy" in legs:
         out["copy_ceiling"] = copy_leg(torch)
     if "cpu" in legs:
-        out["cpu_baseline"] = cpu_baseline_leg(torch, binding, tensors, layer, xs, M)
+        out["cpu_baseline"] = cpu_baseline_leg(torch, binding, tensors, xs, M)
     print(json.dumps(out))
 
 
@@ -262,13 +274,17 @@ def graph_time(torch, fn, n_calls, reps=10):
     return e0.elapsed_time(e1) / (reps * n_calls)
 
 
-def per_shape_leg(torch, binding, tensors, layer, gen):
+def per_shape_leg(torch, binding, tensors, gen):
     """Each shape on its own for M = 1 and M = 8, as a replayed graph: cycling through all resident
     copies of that shape (weights come from HBM), and on one copy only (weights stay in the 256 MB
     last-level cache; labelled as such)."""
     res = []
-    for ti, (name, N, K, copies) in enumerate(layer):
-        same = [t for t in tensors if t[5] == ti]
+    shapes = []
+    for t in tensors:
+        if (t[0], t[1]) not in shapes:
+            shapes.append((t[0], t[1]))
+    for N, K in shapes:
+        same = [t for t in tensors if (t[0], t[1]) == (N, K)]
         for M in (1, 8):
             X = activations(torch, gen, M, K)
             Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
@@ -320,16 +336,17 @@ def copy_leg(torch):
     return {"bytes_read": 4 * n, "bytes_written": 4 * n, "us": round(ms * 1e3, 1), "GBps_read_plus_write": round(8 * n / (ms * 1e-3) / 1e9, 1)}
 
 
-def cpu_baseline_leg(torch, binding, tensors, layer, xs, M):
+def cpu_baseline_leg(torch, binding, tensors, xs, M):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the M = 1 matmuls of
     the first layers' tensors, single thread.  Also checks the GPU result of those calls against it."""
     from oracle import itq3s_ref as ref
 
     ref.build()
-    n_layers = 5 if len(layer) <= 3 else 1  # about 10-20 s of single-thread work
+    per_layer = sum(packed_bytes(t[0], t[1]) for t in tensors if t[4] == 0)
+    n_layers = max(1, min(tensors[-1][4] + 1, int(1.2e9 // per_layer)))  # about 10-20 s of single-thread work
     sample = [t for t in tensors if t[4] < n_layers]
     secs, nbytes, worst = 0.0, 0, 0.0
-    for N, K, codes, scales, li, ti in sample:
+    for N, K, codes, scales, *_ in sample:
         hc, hs = codes.cpu().numpy().view(np.uint32), scales.cpu().numpy().view(np.uint32)
         X = xs[K].cpu().numpy()
         t0 = time.perf_counter()

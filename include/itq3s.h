@@ -99,14 +99,40 @@ int itq3s_matmul(const uint32_t *codes, const uint32_t *scales, int64_t N, int64
                  void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
                  void *stream);
 
-/* Measurement aid: itq3s_matmul with the same arguments, after which the call WAITS for the work and
- * stores in *kernel_ms (HOST pointer) the duration of the contraction kernel alone (the streaming
- * kernel for M <= 16, the tiled kernel otherwise; not the activation-rotation launch in front of it,
- * not launch gaps), taken from HIP events attached to that kernel's dispatch.  Creates and destroys
- * two events per call and is not thread-safe: not for production loops, not capturable in a graph. */
+/* Several weight tensors with the same K against the same activations in ONE call: Y_t = X W_hat_t^T
+ * for t = 0..count-1 (1 <= count <= ITQ3S_MAX_GROUP), e.g. the query/key/value projections of a layer,
+ * or gate and up.  For M <= 16 all tensors are served by a single launch of the streaming kernel, so
+ * the launch latency and the ramp of the memory pipeline are paid once; for larger M the activations
+ * are rotated once and one tiled launch per tensor follows.  Results are identical to count calls of
+ * itq3s_matmul.
+ *   w  [in] HOST array of count descriptors (read during the call, not kept): device pointers codes,
+ *           scales (as for itq3s_matmul), rows N, output Y (M x N of y_dtype, row stride ldy >= N)
+ *   X, M, ldx, y_dtype, status_flags, stream: as for itq3s_matmul
+ *   workspace: at least itq3s_matmul_workspace_bytes(M, max N, K) */
+#define ITQ3S_MAX_GROUP 4
+typedef struct itq3s_weight {
+    const uint32_t *codes;
+    const uint32_t *scales;
+    int64_t N;
+    void *Y;
+    int64_t ldy;
+} itq3s_weight;
+int itq3s_matmul_grouped(const itq3s_weight *w, int count, int64_t K, const void *X, int64_t M, int64_t ldx, int y_dtype,
+                         void *workspace, size_t workspace_bytes, uint32_t *status_flags, void *stream);
+
+/* Measurement aids: itq3s_matmul / itq3s_matmul_grouped with the same arguments, after which the call
+ * WAITS for the work and stores in *kernel_ms (HOST pointer) the duration of the contraction kernel
+ * alone (the streaming kernel for M <= 16; for larger M the first tiled launch; not the
+ * activation-rotation launch in front of it, not launch gaps), taken from HIP events attached to
+ * that kernel's dispatch.  They create and destroy two events per call and are not thread-safe: not
+ * for production loops, not capturable in a graph. */
 int itq3s_matmul_timed(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
                        int64_t ldx, void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes,
                        uint32_t *status_flags, void *stream, float *kernel_ms);
+
+int itq3s_matmul_grouped_timed(const itq3s_weight *w, int count, int64_t K, const void *X, int64_t M, int64_t ldx,
+                               int y_dtype, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
+                               void *stream, float *kernel_ms);
 
 /* Static text for a status code.  Never NULL. */
 const char *itq3s_strerror(int status);

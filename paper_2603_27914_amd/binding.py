@@ -22,10 +22,21 @@ EXPORTS = [
     "itq3s_quantize",
     "itq3s_dequantize",
     "itq3s_matmul",
+    "itq3s_matmul_grouped",
+    "itq3s_matmul_grouped_timed",
     "itq3s_matmul_timed",
     "itq3s_strerror",
     "itq3s_version",
 ]
+
+MAX_GROUP = 4
+
+
+class Weight(ctypes.Structure):
+    """struct itq3s_weight"""
+
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("N", ctypes.c_int64), ("Y", ctypes.c_void_p), ("ldy", ctypes.c_int64)]
+
 
 _lib = None
 
@@ -54,6 +65,10 @@ def lib():
         L.itq3s_dequantize.argtypes = [vp, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul.restype = ci
         L.itq3s_matmul.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
+        L.itq3s_matmul_grouped.restype = ci
+        L.itq3s_matmul_grouped.argtypes = [ctypes.POINTER(Weight), ci, i64, vp, i64, i64, ci, vp, sz, vp, vp]
+        L.itq3s_matmul_grouped_timed.restype = ci
+        L.itq3s_matmul_grouped_timed.argtypes = L.itq3s_matmul_grouped.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_matmul_timed.restype = ci
         L.itq3s_matmul_timed.argtypes = L.itq3s_matmul.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_strerror.restype = ctypes.c_char_p
@@ -131,6 +146,44 @@ def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_
         )
     )
     return out
+
+
+def itq3s_matmul_grouped_timed(weights, K, X, outs=None, dtype=torch.float32, workspace=None, status_flags=None):
+    """itq3s_matmul_grouped, then wait; -> (outs, milliseconds the contraction kernel ran by the GPU's clock)."""
+    ms = ctypes.c_float(0.0)
+    outs = itq3s_matmul_grouped(weights, K, X, outs, dtype, workspace, status_flags, _timed=ms)
+    return outs, float(ms.value)
+
+
+def itq3s_matmul_grouped(weights, K, X, outs=None, dtype=torch.float32, workspace=None, status_flags=None, _timed=None):
+    """weights: list of (codes, scales, N) sharing K -> list of Y_t[M, N_t] = X @ W_hat_t^T, one call."""
+    M = X.shape[0]
+    if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
+        raise Itq3sError("X must be float16 [M, K] with unit column stride")
+    if not 1 <= len(weights) <= MAX_GROUP:
+        raise Itq3sError("1..%d tensors per grouped call" % MAX_GROUP)
+    if outs is None:
+        outs = [torch.empty((M, N), dtype=dtype, device=X.device) for _, _, N in weights]
+    if len(outs) != len(weights) or len({o.dtype for o in outs}) != 1 or outs[0].dtype not in (torch.float32, torch.float16):
+        raise Itq3sError("outs: one float32/float16 tensor per weight tensor, all of one dtype")
+    arr = (Weight * len(weights))()
+    for i, ((codes, scales, N), out) in enumerate(zip(weights, outs)):
+        _need_cuda(codes, scales, out)
+        if out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (M, N):
+            raise Itq3sError("out %d must be [M, N] with unit column stride" % i)
+        arr[i] = Weight(codes.data_ptr(), scales.data_ptr(), N, out.data_ptr(), out.stride(0))
+    _need_cuda(X, workspace, status_flags)
+    if workspace is None:
+        workspace = torch.empty(itq3s_matmul_workspace_bytes(M, max(N for _, _, N in weights), K), dtype=torch.uint8, device=X.device)
+    args = (
+        arr, len(weights), K, _ptr(X), M, X.stride(0), F16 if outs[0].dtype == torch.float16 else F32,
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(status_flags), _stream(),
+    )
+    if _timed is None:
+        _check(lib().itq3s_matmul_grouped(*args))
+    else:
+        _check(lib().itq3s_matmul_grouped_timed(*args, ctypes.byref(_timed)))
+    return outs
 
 
 def itq3s_matmul_timed(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None):

@@ -68,39 +68,55 @@ int itq3s_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, i
     return itq3s::launch_dequantize(codes, scales, N, K, W_out, out_dtype == ITQ3S_F16, ldo, status_flags, static_cast<hipStream_t>(stream));
 }
 
-int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx, void* Y,
-                 int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream) {
-    if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
-    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
-    if ((N + 15) / 16 > 0x7fffffffLL / (K / 256) || M > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
+int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void* X, int64_t M, int64_t ldx, int y_dtype, void* workspace,
+                         size_t workspace_bytes, uint32_t* status_flags, void* stream) {
+    if (!w || !X) return ITQ3S_ERR_NULL;
+    if (count < 1 || count > ITQ3S_MAX_GROUP) return ITQ3S_ERR_SHAPE;
+    if (K <= 0 || M <= 0 || K % 256 != 0 || ldx < K) return ITQ3S_ERR_SHAPE;
     if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
-    if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) ||
-        (status_flags && !aligned(status_flags, 4)))
-        return ITQ3S_ERR_ALIGN;
-    if (!workspace || workspace_bytes < itq3s_matmul_workspace_bytes(M, N, K)) return ITQ3S_ERR_WORKSPACE;
+    if (M > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
+    int64_t n_max = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!w[i].codes || !w[i].scales || !w[i].Y) return ITQ3S_ERR_NULL;
+        if (w[i].N <= 0 || w[i].ldy < w[i].N || (w[i].N + 15) / 16 > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
+        if (!aligned(w[i].codes, 16) || !aligned(w[i].scales, 16) || !aligned(w[i].Y, y_dtype == ITQ3S_F16 ? 2 : 4)) return ITQ3S_ERR_ALIGN;
+        if (w[i].N > n_max) n_max = w[i].N;
+    }
+    if (!aligned(X, 16) || ldx % 8 != 0 || (status_flags && !aligned(status_flags, 4))) return ITQ3S_ERR_ALIGN;
+    if (!workspace || workspace_bytes < itq3s_matmul_workspace_bytes(M, n_max, K)) return ITQ3S_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return ITQ3S_ERR_ALIGN;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const WorkspacePlan p = plan_workspace(M, K);
     _Float16* Xt = static_cast<_Float16*>(workspace);
     const _Float16* Xh = static_cast<const _Float16*>(X);
+    const int y_f16 = y_dtype == ITQ3S_F16;
     if (M <= itq3s::kGemvMaxM) {
+        itq3s::GemvWeight gw[ITQ3S_MAX_GROUP];
+        for (int i = 0; i < count; ++i) gw[i] = itq3s::GemvWeight{w[i].codes, w[i].scales, w[i].N, w[i].Y, w[i].ldy};
         const int MP = pad_m(M);
-        if (itq3s::gemv_can_fuse(M, K))
-            return itq3s::launch_gemv(codes, scales, N, K, Xh, ldx, nullptr, M, MP, true, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+        if (itq3s::gemv_can_fuse(M, K)) return itq3s::launch_gemv(gw, count, K, Xh, ldx, nullptr, M, MP, true, y_f16, status_flags, st);
         float* S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.xt_bytes);
         int rc = itq3s::launch_rotate_frag(Xh, M, K, ldx, MP, Xt, S, st);
         if (rc != 0) return rc;
-        return itq3s::launch_gemv(codes, scales, N, K, Xt, 0, S, M, MP, false, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+        return itq3s::launch_gemv(gw, count, K, Xt, 0, S, M, MP, false, y_f16, status_flags, st);
     }
+    // tiled path: one rotation, then one contraction launch per tensor
     int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, st);
-    if (rc != 0) return rc;
-    return itq3s::launch_gemm(codes, scales, N, K, Xt, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+    for (int i = 0; i < count && rc == 0; ++i) rc = itq3s::launch_gemm(w[i].codes, w[i].scales, w[i].N, K, Xt, M, w[i].Y, y_f16, w[i].ldy, status_flags, st);
+    return rc;
 }
 
-int itq3s_matmul_timed(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
-                       void* Y, int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream,
-                       float* kernel_ms) {
+int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx, void* Y,
+                 int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream) {
+    if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
+    const itq3s_weight w = {codes, scales, N, Y, ldy};
+    return itq3s_matmul_grouped(&w, 1, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream);
+}
+
+int itq3s_matmul_grouped_timed(const itq3s_weight* w, int count, int64_t K, const void* X, int64_t M, int64_t ldx, int y_dtype,
+                               void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream, float* kernel_ms) {
     if (!kernel_ms) return ITQ3S_ERR_NULL;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess) return ITQ3S_ERR_LAUNCH;
@@ -109,14 +125,23 @@ int itq3s_matmul_timed(const uint32_t* codes, const uint32_t* scales, int64_t N,
         return ITQ3S_ERR_LAUNCH;
     }
     itq3s::set_launch_timing(e0, e1);
-    int rc = itq3s_matmul(codes, scales, N, K, X, M, ldx, Y, y_dtype, ldy, workspace, workspace_bytes, status_flags, stream);
-    (void)itq3s::take_launch_timing();  // disarm if validation returned before any launch
-    if (rc == ITQ3S_OK) {
+    int rc = itq3s_matmul_grouped(w, count, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream);
+    const bool taken = itq3s::take_launch_timing().start == nullptr;  // (also disarms if validation returned before any launch)
+    if (rc == ITQ3S_OK && taken) {
         if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(kernel_ms, e0, e1) != hipSuccess) rc = ITQ3S_ERR_LAUNCH;
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     return rc;
+}
+
+int itq3s_matmul_timed(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
+                       void* Y, int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream,
+                       float* kernel_ms) {
+    if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
+    const itq3s_weight w = {codes, scales, N, Y, ldy};
+    return itq3s_matmul_grouped_timed(&w, 1, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream, kernel_ms);
 }
 
 const char* itq3s_strerror(int status) {

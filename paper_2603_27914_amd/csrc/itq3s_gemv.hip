@@ -47,16 +47,25 @@ LaunchTiming take_launch_timing() {
     return t;
 }
 
-struct GemvArgs {
+// One launch serves up to kGemvMaxGroup weight tensors that share K and the activations (the
+// projections of one layer that read the same input): tensor t owns the workgroups from wg_begin on.
+struct GemvTensor {
     const uint32_t* codes;
     const uint32_t* scales;
+    void* Y;
+    int64_t N, ldy;
+    int wg_begin;    // first workgroup of this tensor (0x7fffffff for unused entries)
+    int nt_q, nt_r;  // row tiles per workgroup: the first nt_r workgroups own nt_q + 1, the others nt_q
+    int pad_;
+};
+
+struct GemvArgs {
+    GemvTensor t[kGemvMaxGroup];
     const _Float16* X;  // kFused: activations [M][ldx]; direct: rotated, operand order, MP columns
     const float* S;     // direct only: [KB][MP]
-    void* Y;
     uint32_t* flags;
-    int64_t N, ldx, ldy;
-    int NT, KB, M, y_f16;
-    int nt_q, nt_r;  // row tiles per workgroup: the first nt_r workgroups own nt_q + 1, the others nt_q
+    int64_t ldx;
+    int KB, M, y_f16;
 };
 
 struct TileRegs {
@@ -166,7 +175,9 @@ __device__ __forceinline__ float rotate_to_lds(u32x2 raw, const HadamardOperand&
 }
 
 // NBX = 0: direct; NBX > 0: fused, with room for NBX blocks per wavefront (NBX * MP <= kFusedMaxBlocks).
-template <int MP, int RT, int D, int NBX>
+// kGrouped: the launch serves several tensors (a single-tensor launch skips the lookup and the
+// fetch of the unused descriptors, which are on the way to the first load).
+template <int MP, int RT, int D, int NBX, bool kGrouped>
 __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a) {
     constexpr bool kFused = NBX > 0;
     constexpr int W = kGemvWaves;
@@ -177,11 +188,17 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // wave-uniform, in an SGPR
     const int g = lane >> 4, r16 = lane & 15, mm = r16 & (MP - 1);
-    // RT-1 or RT row tiles (the host picks the grid that way); no division on the way to the first load
-    const int wg = (int)blockIdx.x;
-    const int nt_begin = wg * a.nt_q + (wg < a.nt_r ? wg : a.nt_r);
-    const int cnt = a.nt_q + (wg < a.nt_r ? 1 : 0);
-    const bool full = RT == 1 || cnt == RT;
+    // which tensor (scalar selects over the few entries, all read with the first argument fetch),
+    // then 1..RT row tiles of it; no division and no dependent fetch on the way to the first load
+    GemvTensor T = a.t[0];
+    if constexpr (kGrouped) {
+#pragma unroll
+        for (int i = 1; i < kGemvMaxGroup; ++i)
+            if ((int)blockIdx.x >= a.t[i].wg_begin) T = a.t[i];
+    }
+    const int wg = (int)blockIdx.x - T.wg_begin;
+    const int nt_begin = wg * T.nt_q + (wg < T.nt_r ? wg : T.nt_r);
+    const int cnt = T.nt_q + (wg < T.nt_r ? 1 : 0);
     const int nb = KB > wave ? (KB - wave + W - 1) / W : 0;  // blocks of this wavefront: b = wave + j*W
 
     // LDS: kFused: per wavefront NBX*MP*256 halves of x~, then NBX*MP sums per wavefront; then the
@@ -203,15 +220,14 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     Slot ring[NB];
 
     // loads of step j (block wave + j*W against all row tiles of the workgroup); past the end of
-    // the list, and for the missing last row tile, tile 0 / block 0 stand in (never used)
+    // the list, and for missing row tiles, tile 0 / block 0 stand in (never used)
     auto issue = [&](Slot& s, int j) {
         const bool live = j < nb;
         const int b = wave + j * W;
         const int64_t t0 = live ? (int64_t)nt_begin * KB + b : 0;
         const int64_t step = live ? KB : 0;
 #pragma unroll
-        for (int rt = 0; rt < RT - 1; ++rt) load_tile(s.t[rt], a.codes, a.scales, t0 + rt * step, lane);
-        load_tile(s.t[RT - 1], a.codes, a.scales, full ? t0 + (RT - 1) * step : 0, lane);
+        for (int rt = 0; rt < RT; ++rt) load_tile(s.t[rt], T.codes, T.scales, rt < cnt ? t0 + rt * step : 0, lane);
         if constexpr (!kFused) {
             const int bb = live ? b : 0;
 #pragma unroll
@@ -241,7 +257,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         }
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            if (rt < RT - 1 || full) {
+            if (rt < cnt) {
                 const TileRegs& tr = s.t[rt];
                 const floatx4 c = tile_dot(tr.lo, Xf);
                 bad |= tr.hi.x | tr.hi.y;
@@ -315,20 +331,20 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         const int rr = o % (RT * 16), m = o / (RT * 16);  // rr = rt*16 + r: consecutive threads, consecutive n
         const int rt = rr >> 4;
         const int64_t n = (int64_t)nt_begin * 16 + rr;
-        if (rt < cnt && n < a.N && m < a.M) {
+        if (rt < cnt && n < T.N && m < a.M) {
             float sum = 0.f;
 #pragma unroll
             for (int wv = 0; wv < W; ++wv) sum += red[((wv * RT + rt) * MP + m) * 16 + (rr & 15)];
-            if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)sum;
-            else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = sum;
+            if (a.y_f16) reinterpret_cast<_Float16*>(T.Y)[m * T.ldy + n] = (_Float16)sum;
+            else reinterpret_cast<float*>(T.Y)[m * T.ldy + n] = sum;
         }
     }
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
-template <int MP, int RT, int D, int NBX>
-static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
-    auto kern = gemv_kernel<MP, RT, D, NBX>;
+template <int MP, int RT, int D, int NBX, bool kGrouped>
+static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
+    auto kern = gemv_kernel<MP, RT, D, NBX, kGrouped>;
     static bool lds_limit_raised = false;  // once per instantiation: allow up to the 160 KB of a CU
     if (!lds_limit_raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
@@ -339,6 +355,12 @@ static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+template <int MP, int RT, int D, int NBX>
+static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
+    if (a.t[1].wg_begin != 0x7fffffff) return launch_kernel<MP, RT, D, NBX, true>(a, grid, stream);
+    return launch_kernel<MP, RT, D, NBX, false>(a, grid, stream);
 }
 
 static int cu_count() {
@@ -414,18 +436,60 @@ bool gemv_can_fuse(int64_t M, int64_t K) {
     return mp <= 4 && nb_max * mp <= kFusedMaxBlocks;
 }
 
-int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, const float* S,
-                int64_t M, int MP, bool fused, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
+int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
+                int y_f16, uint32_t* flags, hipStream_t stream) {
+    if (count < 1 || count > kGemvMaxGroup) return -2;
     GemvArgs a;
-    a.codes = codes; a.scales = scales; a.X = X; a.S = S; a.Y = Y; a.flags = flags;
-    a.N = N; a.ldx = ldx; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
-    // one workgroup per CU if that leaves at most kGemvMaxRT row tiles each, else more workgroups
-    const int max_rt = kGemvMaxRT;
-    int grid = a.NT < cu_count() ? a.NT : cu_count();
-    if ((a.NT + grid - 1) / grid > max_rt) grid = (a.NT + max_rt - 1) / max_rt;
-    const int rt = (a.NT + grid - 1) / grid;  // every workgroup gets rt or rt-1 row tiles
-    a.nt_q = a.NT / grid;
-    a.nt_r = a.NT % grid;
+    a.X = X; a.S = S; a.flags = flags; a.ldx = ldx; a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
+    // One workgroup per CU over all tensors if that leaves at most kGemvMaxRT row tiles each, else
+    // more workgroups.  (The kernel's registers allow one workgroup per CU at a time, so a grid just
+    // above the CU count would run a nearly empty second round.)  Every tensor gets its own
+    // workgroups; the split is greedy: the next workgroup goes to the tensor with the most row tiles
+    // per workgroup.
+    int64_t nt[kGemvMaxGroup] = {0, 0, 0, 0}, wgs[kGemvMaxGroup] = {0, 0, 0, 0}, nt_total = 0;
+    for (int i = 0; i < count; ++i) {
+        nt[i] = (w[i].N + 15) / 16;
+        nt_total += nt[i];
+    }
+    int64_t target = nt_total < cu_count() ? nt_total : cu_count();
+    if ((nt_total + target - 1) / target > kGemvMaxRT) target = (nt_total + kGemvMaxRT - 1) / kGemvMaxRT;
+    if (target < count) target = count;
+    int64_t given = 0;
+    for (int i = 0; i < count; ++i) {  // proportional share, rounded down, at least one
+        wgs[i] = nt[i] * target / nt_total;
+        if (wgs[i] < 1) wgs[i] = 1;
+        given += wgs[i];
+    }
+    for (; given < target; ++given) {
+        int best = 0;
+        for (int i = 1; i < count; ++i)
+            if (nt[i] * wgs[best] > nt[best] * wgs[i]) best = i;  // nt[i]/wgs[i] > nt[best]/wgs[best]
+        ++wgs[best];
+    }
+    int rt = 1;
+    for (int i = 0; i < count; ++i) {
+        if ((nt[i] + wgs[i] - 1) / wgs[i] > kGemvMaxRT) wgs[i] = (nt[i] + kGemvMaxRT - 1) / kGemvMaxRT;
+        if (wgs[i] > nt[i]) wgs[i] = nt[i];
+        const int r = (int)((nt[i] + wgs[i] - 1) / wgs[i]);
+        if (r > rt) rt = r;
+    }
+    int64_t grid64 = 0;
+    for (int i = 0; i < kGemvMaxGroup; ++i) {
+        GemvTensor& t = a.t[i];
+        if (i < count) {
+            t.codes = w[i].codes; t.scales = w[i].scales; t.Y = w[i].Y; t.N = w[i].N; t.ldy = w[i].ldy;
+            t.wg_begin = (int)grid64;
+            t.nt_q = (int)(nt[i] / wgs[i]);
+            t.nt_r = (int)(nt[i] % wgs[i]);
+            grid64 += wgs[i];
+        } else {
+            t = a.t[0];
+            t.wg_begin = 0x7fffffff;
+        }
+        t.pad_ = 0;
+    }
+    if (grid64 > 0x7fffffff) return -2;
+    const int grid = (int)grid64;
     const int nb_min = a.KB / kGemvWaves, nb_max = (a.KB + kGemvWaves - 1) / kGemvWaves;
     if (fused) {
         switch (MP) {

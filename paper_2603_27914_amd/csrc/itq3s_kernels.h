@@ -11,6 +11,8 @@ constexpr uint32_t kFlagNonFinite = 1u, kFlagScaleSat = 2u, kFlagZClamp = 4u, kF
 
 // Streaming path handles up to this many activation rows; more rows go to the tiled MFMA path.
 constexpr int kGemvMaxM = 16;
+// One streaming launch serves up to this many weight tensors that share K and the activations.
+constexpr int kGemvMaxGroup = 4;
 
 // Optional device-side timing of the contraction kernel.  set_launch_timing() arms a pair of events;
 // the next launch of a contraction kernel (streaming or tiled) takes them (take_launch_timing clears
@@ -38,10 +40,20 @@ int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx,
 // True if the streaming kernel can rotate the activations itself (one launch, no workspace use).
 bool gemv_can_fuse(int64_t M, int64_t K);
 
+// One weight tensor of a streaming launch and where its product goes.
+struct GemvWeight {
+    const uint32_t* codes;
+    const uint32_t* scales;
+    int64_t N;
+    void* Y;
+    int64_t ldy;
+};
+
+// count (1..kGemvMaxGroup) tensors W_t[N_t, K] against the same activations in one launch.
 // fused: X = activations [M][ldx], S unused.  Otherwise X = rotated activations in operand order with
 // MP columns (from launch_rotate_frag), ldx unused, S = their block sums.
-int launch_gemv(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, const float* S,
-                int64_t M, int MP, bool fused, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
+                int y_f16, uint32_t* flags, hipStream_t stream);
 
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
                 int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);

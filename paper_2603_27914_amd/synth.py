@@ -37,6 +37,22 @@ LLAMA7B_LAYER = [
 ]
 
 
+# The same layers as decode stages: the tensors of one stage read the same activations and are
+# independent of each other (one grouped call); a stage needs the output of the stage before it.
+LLAMA7B_STAGES = [
+    [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096)],
+    [("o", 4096, 4096)],
+    [("gate", 11008, 4096), ("up", 11008, 4096)],
+    [("down", 4096, 11008)],
+]
+LLAMA70B_STAGES = [
+    [("q", 8192, 8192), ("k", 1024, 8192), ("v", 1024, 8192)],
+    [("o", 8192, 8192)],
+    [("gate", 28672, 8192), ("up", 28672, 8192)],
+    [("down", 8192, 28672)],
+]
+
+
 def _rng(*key):
     words = [MASTER_SEED]
     for k in key:

@@ -282,6 +282,61 @@ def test_matmul_timed_variant_same_result_and_positive_time(gpu, ref, M, N, K):
     assert np.array_equal(again, want)
 
 
+GROUPS = [
+    # (K, [N_t], Ms): the projections of a layer that read the same input
+    (4096, [4096, 4096, 4096], (1, 4)),          # 7B query / key / value
+    (4096, [11008, 11008], (1, 8)),              # 7B gate / up
+    (8192, [8192, 1024, 1024], (1, 2, 16)),      # 70B query / key / value (grouped-query attention)
+    (11008, [4096, 40], (1, 3)),                 # long K (rotation launch for M = 3), a tensor with 3 row tiles
+    (512, [16, 1000, 17, 300], (1, 5)),          # four ragged tensors, one with a single row tile
+    (1024, [200, 48], (33,)),                    # tiled path
+]
+
+
+@pytest.mark.parametrize("K,Ns,Ms", GROUPS)
+def test_matmul_grouped_matches_oracle_and_single_calls(gpu, ref, K, Ns, Ms):
+    """One grouped call = the separate calls, bit for bit (same kernels, same order of sums), and
+    within tolerance of the oracle; full rows for the small tensors, sampled rows for the large."""
+    torch, binding = gpu
+    packed = [synth.random_packed(N, K, "grp", i) for i, N in enumerate(Ns)]
+    dev = [(to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)), N) for (c, s), N in zip(packed, Ns)]
+    rng = np.random.default_rng(5)
+    for M in Ms:
+        X = synth.activations(M, K, "grp", M)
+        Xd = to_dev(torch, X)
+        for dtype in (torch.float32, torch.float16):
+            outs = binding.itq3s_matmul_grouped(dev, K, Xd, dtype=dtype)
+            torch.cuda.synchronize()
+            for (c, s), (cd, sd, N), out in zip(packed, dev, outs):
+                single = binding.itq3s_matmul(cd, sd, N, K, Xd, dtype=dtype)
+                assert torch.equal(out, single)
+                if dtype == torch.float32:
+                    if N <= 1024:
+                        spans = [(0, N)]
+                    else:
+                        n0 = int(rng.integers(1, N - 600))
+                        spans = [(0, 200), (n0, n0 + 200), (N - 200, N)]
+                    got = out.cpu().numpy()
+                    for n0, n1 in spans:
+                        want = ref.matmul(c, s, N, K, X, rows=(n0, n1))
+                        assert rel_rows(got[:, n0:n1], want[:, n0:n1]) <= MATMUL_TOL
+
+
+def test_matmul_grouped_rejects_bad_arguments(gpu, ref):
+    torch, binding = gpu
+    K = 512
+    c, s = synth.random_packed(32, K, "grp-bad")
+    dev = (to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)), 32)
+    X = to_dev(torch, synth.activations(1, K, "grp-bad"))
+    with pytest.raises(binding.Itq3sError):
+        binding.itq3s_matmul_grouped([dev] * 5, K, X)
+    with pytest.raises(binding.Itq3sError):
+        binding.itq3s_matmul_grouped([], K, X)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.Itq3sError, match="workspace"):
+        binding.itq3s_matmul_grouped([dev], K, X, workspace=small)
+
+
 def test_matmul_flags_high_plane(gpu, ref):
     torch, binding = gpu
     codes, scales = synth.random_packed(64, 512, "hp")
