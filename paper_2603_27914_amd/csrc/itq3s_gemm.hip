@@ -14,12 +14,17 @@
 // accumulator column is an output channel n and stores are contiguous along n.
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
 namespace itq3s {
 
 constexpr int BM = 128, BN = 128, BK = 64;
+// the 256 x 256 variant below takes over when there are enough rows to fill its tiles and enough
+// tiles to occupy the chip
+constexpr int kGemmBigMinM = 192, kGemmBigMinTiles = 128;
 constexpr int LDT = BK + 8;  // LDS row stride in halves (padding keeps 16-byte reads conflict-free)
 
 struct GemmArgs {
@@ -151,13 +156,245 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Large-M variant: workgroup tile 256 (m) x 256 (n), eight wavefronts as 2 (m) x 4 (n), wavefront
+// tile 128 x 64 = 4 x 2 v_mfma_f32_32x32x16_f16 (128 accumulator registers per lane, two wavefronts
+// per SIMD so that one unpacks while the other multiplies).
+//
+// Only the activations go through LDS (two stages of 256 rows x 64 channels, one barrier per stage).
+// The weights never do: a lane of the 32x32x16 product supplies, for its column n, eight consecutive
+// channels k' of the step -- and one low-plane word of the packed tile holds exactly the 16 channels
+// of one step of one row, in k' order after the shift-and-mask unpack (pairs (slot j, slot j+8)).
+// So every lane loads the words of its own two rows (16 bytes = four steps per load), turns its
+// half of a word into four half2 values d (c - 1 - z) in registers, and feeds the matrix core.  The
+// two wavefronts that share a column range repeat that unpack; in exchange the LDS carries half the
+// traffic and the weight path needs no barrier.
+//
+// Tile order: workgroups are dealt to the 8 chiplets round-robin by the hardware, so chiplet x takes
+// the contiguous run [x * per, (x+1) * per) of the tile list (m fastest): the workgroups that run
+// together on one chiplet share their weight columns and the activation slab in that chiplet's L2.
+constexpr int GM = 256, GN = 256, GK = 64;
+constexpr int GLD = GK + 8;  // LDS row stride in halves: 144 bytes, conflict-free for 16-byte reads
+constexpr int GT = 512;      // threads
+constexpr int kGemmBigLds = 2 * GM * GLD * 2;  // bytes, dynamic (above the 64 KB static limit)
+
+__global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
+    extern __shared__ __align__(16) _Float16 As[];  // [2][GM * GLD]
+
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int t = xcd * per_chiplet + slot;
+    if (slot >= per_chiplet || t >= tiles_m * tiles_n) return;
+    const int tn = t / tiles_m, tm = t - tn * tiles_m;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int64_t m0 = (int64_t)tm * GM;
+    const int64_t n0 = (int64_t)tn * GN;
+
+    // Every load below is unconditional (rows past M or N and steps past K are clamped to valid
+    // memory; what they produce lands in outputs that are never stored), so the loop is straight-line
+    // and the load counter alone orders loads and use.
+    // ---- activation loader: four 16-byte pieces per thread and stage (row = idx/8, piece = idx%8),
+    // loaded one stage (four MFMA steps) before they are written to LDS
+    u32x4 xa0, xa1, xa2, xa3;  // (plain variables: an array shared by two lambdas stays in memory)
+    const int xr = tid >> 3, xc = tid & 7;  // rows xr, xr+64, xr+128, xr+192
+    const _Float16* xrow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xrow[i] = a.Xt + (m0 + xr + 64 * i < a.M ? m0 + xr + 64 * i : a.M - 1) * a.K + xc * 8;
+    const int KT = (int)(a.K / GK);
+    auto load_x = [&](int kt) {
+        const int k = (kt < KT ? kt : KT - 1) * GK;
+        xa0 = *reinterpret_cast<const u32x4*>(xrow[0] + k);
+        xa1 = *reinterpret_cast<const u32x4*>(xrow[1] + k);
+        xa2 = *reinterpret_cast<const u32x4*>(xrow[2] + k);
+        xa3 = *reinterpret_cast<const u32x4*>(xrow[3] + k);
+    };
+    auto store_x = [&](int stage) {
+        _Float16* dst = As + stage * (GM * GLD) + xr * GLD + xc * 8;
+        *reinterpret_cast<u32x4*>(dst) = xa0;
+        *reinterpret_cast<u32x4*>(dst + 64 * GLD) = xa1;
+        *reinterpret_cast<u32x4*>(dst + 128 * GLD) = xa2;
+        *reinterpret_cast<u32x4*>(dst + 192 * GLD) = xa3;
+    };
+
+    // ---- weight loader: this lane's two rows n = n0 + wn*64 + j*32 + l32.  Row j sits 2j tile rows
+    // below row 0; offsets are 32-bit, relative to the workgroup's first tile row (its 16 tile rows
+    // span 16*KB tiles, far below 2^31 words for any K this library accepts).
+    const int64_t nt0 = n0 >> 4;
+    const uint32_t* const wg_codes = a.codes + nt0 * a.KB * kTileWords;
+    const uint32_t* const wg_scales = a.scales + nt0 * a.KB * kTileRows;
+    const int r16 = l32 & 15;
+    uint32_t woff[2], soff[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        int64_t tr = wn * 4 + (l32 >> 4) + 2 * j;
+        if (nt0 + tr > a.NT - 1) tr = a.NT - 1 - nt0;
+        woff[j] = (uint32_t)tr * (uint32_t)a.KB * kTileWords + 4 * r16;
+        soff[j] = (uint32_t)tr * (uint32_t)a.KB * kTileRows + r16;
+    }
+    uint32_t bad = 0;
+    const int QT = KT;  // quarters of a block: 64 channels = one LDS stage = four MFMA steps
+    uint2 hi0, hi1;  // high-plane words of the quarter in flight; folded into `bad` a stage later
+    auto load_w = [&](int qt_, uint4 (&w)[2], uint32_t (&sc)[2]) {  // quarter of the row: block qt/4, quarter qt%4
+        const int qt = qt_ < QT ? qt_ : QT - 1;
+        const uint32_t b = (uint32_t)qt >> 2, q = (uint32_t)qt & 3;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t* tile = wg_codes + (woff[j] + b * kTileWords);  // low-plane words of lane 16q + r16 start at + 64q
+            w[j] = *reinterpret_cast<const uint4*>(tile + 64 * q);
+            (j == 0 ? hi0 : hi1) = *reinterpret_cast<const uint2*>(tile + kTileLoWords + 32 * q - 2 * r16);
+            sc[j] = wg_scales[soff[j] + b * kTileRows];
+        }
+    };
+    // Unpack: a code OR-ed into the mantissa of 1024.0 (bit pattern 0x6400, unit in the last place 1)
+    // is the half 1024 + c; adding -(1025 + z) gives c - 1 - z exactly (for |1025 + z| <= 2048; beyond
+    // that the constant rounds to an even integer, an error of 1 in 2000), times d.
+    half2v dd[2], off[2];  // per row: d and -(1025 + z) of the block being unpacked
+    auto set_scale = [&](const uint32_t (&sc)[2]) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(sc[j] & 0xffffu));
+            const _Float16 o = (_Float16)(-1025.0f - (float)__builtin_bit_cast(_Float16, (uint16_t)(sc[j] >> 16)));
+            dd[j] = half2v{d, d};
+            off[j] = half2v{o, o};
+        }
+    };
+    // word = the 16 channels of one MFMA step of row j; this lane's eight are the pairs 4kg .. 4kg+3
+    auto unpack = [&](uint32_t word, int j) -> half8 {
+        const uint32_t v = word >> (8 * kg);
+        uint32_t o[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            half2v h = __builtin_bit_cast(half2v, ((v >> (2 * p)) & 0x00030003u) | 0x64006400u);
+            h = (h + off[j]) * dd[j];
+            o[p] = __builtin_bit_cast(uint32_t, h);
+        }
+        const uint4 u = make_uint4(o[0], o[1], o[2], o[3]);
+        return __builtin_bit_cast(half8, u);
+    };
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // One MFMA step: 4 x 2 products on the fragments af (activations, read from LDS a step earlier)
+    // and bf (weights), while the activation fragments of the next step are read into an and the
+    // weights of the NEXT step (words nw0, nw1 of rows 0, 1) are unpacked into bf for the step after
+    // -- the unpack belongs to no LDS stage, so that pipeline runs straight through the barriers.
+    // The scheduling groups ask for the order: the LDS reads, then one matrix instruction and five
+    // vector instructions, eight times.
+    half8 bf[2];
+    const _Float16* const a_lane = As + (wm * 128 + l32) * GLD + kg * 8;  // + stage*GM*GLD + i*32*GLD + ks*16
+    auto read_a = [&](int stage, int ks, half8 (&af)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const half8*>(a_lane + stage * (GM * GLD) + i * 32 * GLD + ks * 16);
+    };
+    auto step = [&](const half8 (&af)[4], uint32_t nw0, uint32_t nw1) {
+        const half8 n0v = unpack(nw0, 0), n1v = unpack(nw1, 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        bf[0] = n0v;
+        bf[1] = n1v;
+    };
+    auto interleave = [&](int ds_reads) {
+        if (ds_reads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        }
+    };
+
+    // Stage qt (64 channels = a quarter of a block) lives in LDS buffer qt & 1.  While it is
+    // multiplied, the activations and the weights of stage qt+1 are on their way; the scheduling
+    // fences keep the loads where they are written (the compiler would sink them next to their use
+    // and wait for them at once).
+    uint4 wcur[2], wnext[2];
+    uint32_t sc_next[2];
+    half8 af0[4], af1[4];
+    load_x(0);
+    load_w(0, wcur, sc_next);
+    set_scale(sc_next);
+    bad |= hi0.x | hi0.y | hi1.x | hi1.y;
+    bf[0] = unpack(wcur[0].x, 0);
+    bf[1] = unpack(wcur[1].x, 1);
+    store_x(0);
+    __syncthreads();
+    for (int qt = 0; qt < QT; ++qt) {
+        const int stage = qt & 1;
+        load_x(qt + 1);
+        load_w(qt + 1, wnext, sc_next);
+        read_a(stage, 0, af0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(stage, 1, af1);
+        step(af0, wcur[0].y, wcur[1].y);
+        interleave(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(stage, 2, af0);
+        step(af1, wcur[0].z, wcur[1].z);
+        interleave(1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(stage, 3, af1);
+        step(af0, wcur[0].w, wcur[1].w);
+        interleave(1);
+        __builtin_amdgcn_sched_barrier(0);
+        set_scale(sc_next);  // the next quarter may start a new block
+        bad |= hi0.x | hi0.y | hi1.x | hi1.y;
+        __builtin_amdgcn_sched_barrier(0);
+        step(af1, wnext[0].x, wnext[1].x);
+        interleave(0);
+        __builtin_amdgcn_sched_barrier(0);
+        store_x(stage ^ 1);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) wcur[j] = wnext[j];
+        __syncthreads();
+    }
+
+    // accumulator register v of a 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t n = n0 + wn * 64 + j * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t m = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                if (m < a.M && n < a.N) {
+                    if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[i][j][v];
+                    else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[i][j][v];
+                }
+            }
+        }
+    if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
+}
+
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
                 int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
     GemmArgs a;
     a.codes = codes; a.scales = scales; a.Xt = Xt; a.Y = Y; a.flags = flags;
     a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
-    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     const LaunchTiming tm = take_launch_timing();
+    const int64_t tiles_m = (M + GM - 1) / GM, tiles_n = (N + GN - 1) / GN;
+    if (M >= kGemmBigMinM && tiles_m * tiles_n >= kGemmBigMinTiles && tiles_m * tiles_n < 0x7fffffff / 8) {
+        const int per = (int)((tiles_m * tiles_n + 7) / 8);
+        const dim3 g((unsigned)(per * 8));
+        static bool lds_limit_raised = false;
+        if (!lds_limit_raised) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmBigLds) != hipSuccess) return -6;
+            lds_limit_raised = true;
+        }
+        if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmBigLds, stream, tm.start, tm.stop, 0, a, (int)tiles_m, (int)tiles_n, per);
+        else hipLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmBigLds, stream, a, (int)tiles_m, (int)tiles_n, per);
+        return hipGetLastError() == hipSuccess ? 0 : -6;
+    }
+    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
     if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;

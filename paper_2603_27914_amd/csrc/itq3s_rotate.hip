@@ -3,32 +3,43 @@
 // instead of transforming every weight block, each 256-channel chunk of the activations is
 // transformed once per call and the ternary digits are contracted with the rotated chunk.
 //
-// One wavefront per (row m, chunk b); lane l holds elements 4l..4l+3 in fp32, butterflies as in the
-// weight-side kernels, one rounding to fp16 at the end.
+// One wavefront per (row m, chunk b).  The 256-point transform runs on the matrix cores: with the
+// chunk written as a 16 x 16 matrix X[a][b] = x[16a + b], the Sylvester construction gives
+// H_256 = H_16 (x) H_16, i.e. (H x)[16a' + b'] = (H_16 X H_16)[a'][b'] / 16 (H_16 with entries +-1).
+// T = X (H_16/4) is one 16x16x16 product (fp16 inputs, exact products, fp32 sums; the factor keeps
+// |T| <= 4 max|x| inside the fp16 range); H_16 T follows with T split into two halves
+// (T = T_hi + T_lo keeps 22 bits), then the remaining factor 1/4 and one rounding to fp16.  The
+// accumulator layout of the first product is the B-operand layout of the second, so nothing moves
+// between lanes.
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
 namespace itq3s {
 
-// x~ = H x for one chunk; returns the four rounded values of this lane.
+// x~ = H x for one chunk.  Lane l reads x[16 (l%16) + 4 (l/16) + 0..3] and returns the rounded
+// elements e = 64 (l/16) + 16 i + l%16, i = 0..3.
 __device__ __forceinline__ void rotate_chunk(const _Float16* __restrict__ src, int lane, _Float16 out[4]) {
-    const half4 h = *reinterpret_cast<const half4*>(src + 4 * lane);
-    float v0 = (float)h[0], v1 = (float)h[1], v2 = (float)h[2], v3 = (float)h[3];
-    float t0 = v0 + v1, t1 = v0 - v1, t2 = v2 + v3, t3 = v2 - v3;
-    v0 = t0 + t2; v2 = t0 - t2; v1 = t1 + t3; v3 = t1 - t3;
+    const int r16 = lane & 15, g = lane >> 4;
+    half4 h, q;  // H_16[4g + j][r16] and a quarter of it
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-        const bool upper = (lane & m) != 0;
-        const float p0 = xor_lane_f32(v0, m), p1 = xor_lane_f32(v1, m), p2 = xor_lane_f32(v2, m), p3 = xor_lane_f32(v3, m);
-        v0 = upper ? (p0 - v0) : (v0 + p0);
-        v1 = upper ? (p1 - v1) : (v1 + p1);
-        v2 = upper ? (p2 - v2) : (v2 + p2);
-        v3 = upper ? (p3 - v3) : (v3 + p3);
+    for (int j = 0; j < 4; ++j) {
+        const bool neg = (__builtin_popcount((4 * g + j) & r16) & 1) != 0;
+        h[j] = neg ? (_Float16)(-1.0f) : (_Float16)1.0f;
+        q[j] = neg ? (_Float16)(-0.25f) : (_Float16)0.25f;
     }
-    out[0] = (_Float16)(v0 * 0.0625f);
-    out[1] = (_Float16)(v1 * 0.0625f);
-    out[2] = (_Float16)(v2 * 0.0625f);
-    out[3] = (_Float16)(v3 * 0.0625f);
+    const half4 xa = *reinterpret_cast<const half4*>(src + 16 * r16 + 4 * g);
+    const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+    const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(xa, q, zero, 0, 0, 0);
+    half4 th, tl;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        th[j] = (_Float16)T[j];
+        tl[j] = (_Float16)(T[j] - (float)th[j]);
+    }
+    floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);
+    U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, tl, U, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = (_Float16)(U[i] * 0.25f);
 }
 
 // Operand order of the streaming kernel.  The 16x16x32 MFMA of step t (0..7) takes from lane
@@ -51,7 +62,7 @@ __global__ __launch_bounds__(256) void rotate_frag_kernel(const _Float16* __rest
     if (lane == 0) S[b * MP + m] = s;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int e = 4 * lane + j;
+        const int e = 64 * (lane >> 4) + 16 * j + (lane & 15);
         const int g = e >> 6, w = (e >> 4) & 3, slot = e & 15;
         const int t = 2 * w + ((slot & 7) >> 2);
         const int i = 2 * (slot & 3) + (slot >> 3);
@@ -73,7 +84,7 @@ __global__ __launch_bounds__(256) void rotate_rowmajor_kernel(const _Float16* __
     _Float16* dst = Xt + m * K + b * kBlock;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int e = 4 * lane + j, s = e & 15;
+        const int e = 64 * (lane >> 4) + 16 * j + (lane & 15), s = e & 15;
         dst[(e & ~15) | (2 * (s & 7) + (s >> 3))] = r[j];
     }
 }
