@@ -1,9 +1,17 @@
 // Weight-side reconstruction (Alg. 2, Prop. 1): w_hat = H( d (q - z) ).
 //
-// q - z takes small integer values, so the eight butterfly stages run in int32 and are exact; the
-// zero-point only reaches element 0 (H applied to a constant vector is a spike: H 1 = 16 e_0) and
-// is folded in after the transform.  One rounding per output element.  One wavefront per block,
-// lane l holds elements 4l..4l+3; a workgroup of four wavefronts covers one 16-row tile.
+// q takes small integer values, so the transform of the digits is exact in any arithmetic that holds
+// integers up to 512; the zero-point only reaches element 0 (H applied to a constant vector is a
+// spike: H 1 = 16 e_0) and is folded in after the transform.  One rounding per output element.
+//
+// The 256-point transform runs on the matrix cores.  With the block written as a 16 x 16 matrix
+// V[a][b] = v[16a + b], the Sylvester construction gives H_256 = H_16 (x) H_16, so
+// (H_u v)[16a' + b'] = (H_16 V H_16)[a'][b'] with the +-1 matrix H_16.  The kernel forms the
+// transpose, U^T = H_16 (V^T H_16): two 16x16x16 products on fp16 inputs (digits, then integers up
+// to 32: all exact) with fp32 sums.  The accumulator layout of the first product is the B-operand
+// layout of the second, and the transposed result leaves every lane with four consecutive output
+// elements, e = 16 (l%16) + 4 (l/16) + 0..3: a wavefront stores one contiguous row segment.
+// One wavefront per block; a workgroup of four wavefronts covers one 16-row tile, four rows each.
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
@@ -11,70 +19,75 @@ namespace itq3s {
 
 template <bool kOutF16>
 __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scales,
-                                                         int64_t N, int64_t K, void* __restrict__ out, int64_t ldo,
+                                                         int64_t N, int KB, void* __restrict__ out, int64_t ldo,
                                                          uint32_t* __restrict__ flags) {
-    const int64_t KB = K / kBlock;
-    const int64_t tile = blockIdx.x;
-    const int64_t nt = tile / KB, b = tile - nt * KB;
+    const int tile = (int)blockIdx.x;
+    const int nt = tile / KB, b = tile - nt * KB;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const uint32_t* t = codes + tile * kTileWords;
-    const int g = lane >> 4, w = (lane >> 2) & 3, q4 = lane & 3;
-    bool bad = false;
+    const int r16 = lane & 15, g = lane >> 4;
+    const uint32_t* t = codes + (int64_t)tile * kTileWords;
 
+    half4 h;  // H_16[4g + j][r16]: B operand of the first product, A operand of the second
+#pragma unroll
+    for (int j = 0; j < 4; ++j) h[j] = (__builtin_popcount((4 * g + j) & r16) & 1) ? (_Float16)(-1.0f) : (_Float16)1.0f;
+
+    // the four rows of this wavefront: loads first, arithmetic after
+    u32x4 lo[4];
+    u32x2 hi[4];
+    uint32_t sw[4];
+#pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int r = wave * 4 + rr;
-        const int64_t n = nt * kTileRows + r;
+        // elements e = 64 g + 16 j + r16 (j = 0..3) sit in slot r16 of low-plane word j of storage lane
+        // 16 g + r; their high bits in bit 16 (j & 1) + r16 of high-plane word j >> 1
+        lo[rr] = *reinterpret_cast<const u32x4*>(t + 4 * (16 * g + r));
+        hi[rr] = *reinterpret_cast<const u32x2*>(t + kTileLoWords + 2 * (16 * g + r));
+        sw[rr] = scales[(int64_t)tile * kTileRows + r];
+    }
+    bool bad = false;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = wave * 4 + rr;
+        const int64_t n = (int64_t)nt * kTileRows + r;
         if (n >= N) break;
-        const uint32_t lo = t[4 * (16 * g + r) + w];
-        const uint32_t hi = t[kTileLoWords + 2 * (16 * g + r) + (w >> 1)];
-        const uint32_t sw = scales[tile * kTileRows + r];
-        const uint32_t lo_byte = (lo >> (8 * q4)) & 0xffu;
-        const uint32_t hi_nib = (hi >> (16 * (w & 1) + 4 * q4)) & 0xfu;
-        int v[4];
+        const uint32_t lw[4] = {lo[rr].x, lo[rr].y, lo[rr].z, lo[rr].w};
+        const uint32_t hw[2] = {hi[rr].x, hi[rr].y};
+        half4 v;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t c = ((lo_byte >> (2 * i)) & 3u) | (((hi_nib >> i) & 1u) << 2);
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t c = ((lw[j] >> (2 * r16)) & 3u) | (((hw[j >> 1] >> (16 * (j & 1) + r16)) & 1u) << 2);
             bad |= c > 2u;
-            v[i] = (int)c - 1;
+            v[j] = (_Float16)(float)((int)c - 1);
         }
-        // unnormalised Hadamard butterflies: distances 1, 2 in registers, 4..128 across lanes
-        int t0 = v[0] + v[1], t1 = v[0] - v[1], t2 = v[2] + v[3], t3 = v[2] - v[3];
-        v[0] = t0 + t2; v[2] = t0 - t2; v[1] = t1 + t3; v[3] = t1 - t3;
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) {
-            const bool upper = (lane & m) != 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int p = xor_lane_i32(v[i], m);
-                v[i] = upper ? (p - v[i]) : (v[i] + p);
-            }
-        }
-        const float d = f16_bits_to_f32(sw & 0xffffu);
-        const float z = f16_bits_to_f32(sw >> 16);
-        float f[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = (float)v[i];
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+        const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(v, h, zero, 0, 0, 0);  // V^T H_16, |.| <= 16 * 6
+        const half4 th = {(_Float16)T[0], (_Float16)T[1], (_Float16)T[2], (_Float16)T[3]};
+        const floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);
+        const float d = f16_bits_to_f32(sw[rr] & 0xffffu);
+        const float z = f16_bits_to_f32(sw[rr] >> 16);
+        float f[4] = {U[0], U[1], U[2], U[3]};
         if (lane == 0) f[0] = f[0] - 256.0f * z;  // H_u applied to the constant -z
 #pragma unroll
         for (int i = 0; i < 4; ++i) f[i] = (d * f[i]) * 0.0625f;
-        const int64_t off = n * ldo + b * kBlock + 4 * lane;
+        const int64_t off = n * ldo + (int64_t)b * kBlock + 16 * r16 + 4 * g;
         if (kOutF16) {
-            half4 h = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
-            *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(out) + off) = h;
+            half4 o = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
+            *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(out) + off) = o;
         } else {
             *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + off) = make_float4(f[0], f[1], f[2], f[3]);
         }
     }
-    if (flags != nullptr && bad) atomicOr(flags, kFlagBadCode);
+    if (flags != nullptr && __builtin_amdgcn_ballot_w64(bad) != 0ull && lane == 0) atomicOr(flags, kFlagBadCode);
 }
 
 int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* out, int out_f16, int64_t ldo,
                       uint32_t* flags, hipStream_t stream) {
     const int64_t tiles = ((N + 15) / 16) * (K / kBlock);
+    const int KB = (int)(K / kBlock);
     if (out_f16)
-        hipLaunchKernelGGL(dequantize_kernel<true>, dim3((unsigned)tiles), dim3(256), 0, stream, codes, scales, N, K, out, ldo, flags);
+        hipLaunchKernelGGL(dequantize_kernel<true>, dim3((unsigned)tiles), dim3(256), 0, stream, codes, scales, N, KB, out, ldo, flags);
     else
-        hipLaunchKernelGGL(dequantize_kernel<false>, dim3((unsigned)tiles), dim3(256), 0, stream, codes, scales, N, K, out, ldo, flags);
+        hipLaunchKernelGGL(dequantize_kernel<false>, dim3((unsigned)tiles), dim3(256), 0, stream, codes, scales, N, KB, out, ldo, flags);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -1,9 +1,14 @@
-// Offline quantizer (Alg. 1, Def. 1): one wavefront per 256-element block, fp64 arithmetic in a
-// fixed order so that the packed output is bit-identical on any IEEE-754 machine.
+// Offline quantizer (Alg. 1, Def. 1) in fp64, every operation in a fixed order so that the packed
+// output is bit-identical on any IEEE-754 machine.
 //
-// Lane l holds elements 4l..4l+3.  Butterfly stages with distance 1 and 2 stay inside the lane,
-// distances 4..128 exchange with lane l^1 .. l^32.  This file must be compiled with floating
-// point contraction off: every add, subtract and multiply below rounds on its own.
+// A block (256 consecutive channels of one row) is held by 16 lanes, 16 consecutive elements each:
+// a wavefront works on four rows of a storage tile at once, a workgroup of four wavefronts on the
+// whole 16-row tile.  Butterfly stages with distance 1, 2, 4, 8 stay inside the lane; distances
+// 16 .. 128 exchange with lane l^1, l^2, l^4, l^8 of the same row of 16 lanes, which are
+// data-parallel-primitive moves (no LDS traffic).  The 16 codes of a lane are exactly one low-plane
+// word of the packed tile, so the result is stored straight from registers.  This file must be
+// compiled with floating point contraction off: every add, subtract and multiply below rounds on
+// its own.
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
@@ -11,97 +16,156 @@ namespace itq3s {
 
 constexpr double kTStar = 0.7979;  // optimal ternary scale / sigma (Sec. 3.3, App. A)
 
-// Sum over the 256 elements of a block, pairwise: neighbours first, then distance 2, 4, ... 128.
-// Addition is commutative bit for bit, so every lane ends with the same value.
-__device__ __forceinline__ double block_pairwise_sum(double v0, double v1, double v2, double v3) {
-    double t = (v0 + v1) + (v2 + v3);
+// value of lane (l ^ MASK), MASK in {1, 2, 4, 8}: moves inside a row of 16 lanes
+template <int MASK>
+__device__ __forceinline__ int row_xor_i32(int x) {
+    // (every lane reads a valid lane, so no previous value of the destination is needed)
+    if constexpr (MASK == 1) return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true);       // quad_perm [1,0,3,2]
+    else if constexpr (MASK == 2) return __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
+    else if constexpr (MASK == 4) {  // l^7 (mirror in 8) then l^3 (reverse in 4)
+        x = __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true);
+        return __builtin_amdgcn_mov_dpp(x, 0x1B, 0xf, 0xf, true);
+    } else {  // l^15 (mirror in 16) then l^7
+        x = __builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true);
+        return __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true);
+    }
+}
+template <int MASK>
+__device__ __forceinline__ double row_xor_f64(double v) {
+    const int lo = row_xor_i32<MASK>(__double2loint(v)), hi = row_xor_i32<MASK>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+// One cross-lane butterfly stage: the lower lane of a pair gets u + v, the upper one u - v (u the
+// lower lane's value).  The upper lane forms (-v) + u, which is u - v bit for bit.
+template <int MASK>
+__device__ __forceinline__ void cross_stage(double (&a)[16], int l16) {
+    const int flip = (l16 & MASK) ? (int)0x80000000u : 0;
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) t = t + xor_lane_f64(t, m);
-    return t;
+    for (int i = 0; i < 16; ++i) {
+        const double p = row_xor_f64<MASK>(a[i]);
+        const double s = __hiloint2double(__double2hiint(a[i]) ^ flip, __double2loint(a[i]));
+        a[i] = s + p;
+    }
+}
+
+// Sum over the 256 elements of a block, pairwise: neighbours first, then distance 2, 4, ... 128.
+// Addition is commutative bit for bit, so every lane of the row ends with the same value.
+__device__ __forceinline__ double block_pairwise_sum(const double (&v)[16]) {
+    double t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = v[2 * i] + v[2 * i + 1];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = t[2 * i] + t[2 * i + 1];
+    t[0] = t[0] + t[1];
+    t[1] = t[2] + t[3];
+    double s = t[0] + t[1];
+    s = s + row_xor_f64<1>(s);
+    s = s + row_xor_f64<2>(s);
+    s = s + row_xor_f64<4>(s);
+    s = s + row_xor_f64<8>(s);
+    return s;
 }
 
 __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ W, int64_t N, int64_t K, int64_t ldw,
                                                        uint32_t* __restrict__ codes, uint32_t* __restrict__ scales,
-                                                       uint32_t* __restrict__ flags) {
-    __shared__ uint32_t tile_lds[kTileWords];
-    __shared__ uint32_t scale_lds[kTileRows];
-
-    const int64_t KB = K / kBlock;
-    const int64_t tile = blockIdx.x;  // nt * KB + b
-    const int64_t nt = tile / KB, b = tile - nt * KB;
+                                                       uint32_t* __restrict__ flags, int KB) {
+    const int tile = (int)blockIdx.x;  // nt * KB + b
+    const int nt = tile / KB, b = tile - nt * KB;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, r = 4 * wave + (lane >> 4);
+    const int64_t n = (int64_t)nt * kTileRows + r;
+    uint32_t* const out = codes + (int64_t)tile * kTileWords;
 
-    if (threadIdx.x < kTileWords - kTileLoWords) tile_lds[kTileLoWords + threadIdx.x] = 0u;  // high plane: always 0
+    // high plane: always 0 on encode (128 words, threads 0..127)
+    if (threadIdx.x < kTileWords - kTileLoWords) out[kTileLoWords + threadIdx.x] = 0u;
+
     uint32_t my_flags = 0;
-
-    for (int rr = 0; rr < 4; ++rr) {
-        const int r = wave * 4 + rr;
-        const int64_t n = nt * kTileRows + r;
-        uint32_t code_byte = 0x55u;  // four codes "1" = digit 0
-        uint32_t word = 0u;
-        if (n < N) {
-            const float4 w4 = *reinterpret_cast<const float4*>(W + n * ldw + b * kBlock + 4 * lane);
-            double a0 = (double)w4.x, a1 = (double)w4.y, a2 = (double)w4.z, a3 = (double)w4.w;
-            const bool finite = isfinite(w4.x) && isfinite(w4.y) && isfinite(w4.z) && isfinite(w4.w);
-            if (__builtin_amdgcn_ballot_w64(!finite) != 0ull) {
-                my_flags |= kFlagNonFinite;
-            } else {
-                // w' = H w: stages 1, 2 in registers ...
-                double t0 = a0 + a1, t1 = a0 - a1, t2 = a2 + a3, t3 = a2 - a3;
-                a0 = t0 + t2; a2 = t0 - t2; a1 = t1 + t3; a3 = t1 - t3;
-                // ... stages 4 .. 128 across lanes: the lower index gets u+v, the higher one u-v
+    uint32_t lo_word = 0x55555555u;  // sixteen codes "1" = digit 0
+    uint32_t scale_word = 0u;
+    if (n < N) {  // (uniform over the 16 lanes of a row; the moves below never leave the row)
+        const float4* src = reinterpret_cast<const float4*>(W + n * ldw + (int64_t)b * kBlock + 16 * l16);
+        const float4 w0 = src[0], w1 = src[1], w2 = src[2], w3 = src[3];
+        const float wf[16] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w, w2.x, w2.y, w2.z, w2.w, w3.x, w3.y, w3.z, w3.w};
+        bool finite = true;
+        double a[16];
 #pragma unroll
-                for (int m = 1; m < 64; m <<= 1) {
-                    const bool upper = (lane & m) != 0;
-                    const double p0 = xor_lane_f64(a0, m), p1 = xor_lane_f64(a1, m);
-                    const double p2 = xor_lane_f64(a2, m), p3 = xor_lane_f64(a3, m);
-                    a0 = upper ? (p0 - a0) : (a0 + p0);
-                    a1 = upper ? (p1 - a1) : (a1 + p1);
-                    a2 = upper ? (p2 - a2) : (a2 + p2);
-                    a3 = upper ? (p3 - a3) : (a3 + p3);
-                }
-                a0 = a0 * 0.0625; a1 = a1 * 0.0625; a2 = a2 * 0.0625; a3 = a3 * 0.0625;
-
-                const double mu = block_pairwise_sum(a0, a1, a2, a3) / 256.0;
-                const double e0 = a0 - mu, e1 = a1 - mu, e2 = a2 - mu, e3 = a3 - mu;
-                const double sigma = sqrt(block_pairwise_sum(e0 * e0, e1 * e1, e2 * e2, e3 * e3) / 256.0);
-                double d64 = kTStar * sigma;
-                if (d64 > 65504.0) { d64 = 65504.0; my_flags |= kFlagScaleSat; }
-                const _Float16 dh = (_Float16)(float)d64;  // two roundings to nearest even, as specified
-                const double d = (double)dh;
-                if (d > 0.0) {
-                    const double rnd = floor(mu / d + 0.5);
-                    double z = 0.0 - rnd;
-                    if (z > 2048.0) { z = 2048.0; my_flags |= kFlagZClamp; }
-                    if (z < -2048.0) { z = -2048.0; my_flags |= kFlagZClamp; }
-                    const double t_hi = (0.5 - z) * d, t_lo = (-0.5 - z) * d;  // exact products
-                    const uint32_t c0 = a0 >= t_hi ? 2u : (a0 < t_lo ? 0u : 1u);
-                    const uint32_t c1 = a1 >= t_hi ? 2u : (a1 < t_lo ? 0u : 1u);
-                    const uint32_t c2 = a2 >= t_hi ? 2u : (a2 < t_lo ? 0u : 1u);
-                    const uint32_t c3 = a3 >= t_hi ? 2u : (a3 < t_lo ? 0u : 1u);
-                    code_byte = c0 | (c1 << 2) | (c2 << 4) | (c3 << 6);
-                    const _Float16 zh = (_Float16)(float)z;
-                    word = (uint32_t)__builtin_bit_cast(uint16_t, dh) | ((uint32_t)__builtin_bit_cast(uint16_t, zh) << 16);
-                }
-            }
+        for (int i = 0; i < 16; ++i) {
+            finite = finite && isfinite(wf[i]);
+            a[i] = (double)wf[i];
         }
-        // elements 4l..4l+3 of row r: low-plane word 4*(16*(l>>4) + r) + ((l>>2)&3), byte l&3
-        const int word_idx = 4 * (16 * (lane >> 4) + r) + ((lane >> 2) & 3);
-        reinterpret_cast<unsigned char*>(tile_lds)[4 * word_idx + (lane & 3)] = (unsigned char)code_byte;
-        if (lane == 0) scale_lds[r] = word;
+        // any non-finite weight among the 16 lanes of this row?
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(!finite);
+        const bool row_bad = ((bal >> (lane & 48)) & 0xffffull) != 0ull;
+
+        // w' = H w: stages 1, 2, 4, 8 in registers (the lower index gets u+v, the higher one u-v) ...
+#pragma unroll
+        for (int s = 1; s < 16; s <<= 1)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if ((i & s) == 0) {
+                    const double u = a[i], v = a[i + s];
+                    a[i] = u + v;
+                    a[i + s] = u - v;
+                }
+        // ... stages 16 .. 128 across the lanes of the row
+        cross_stage<1>(a, l16);
+        cross_stage<2>(a, l16);
+        cross_stage<4>(a, l16);
+        cross_stage<8>(a, l16);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a[i] = a[i] * 0.0625;
+
+        const double mu = block_pairwise_sum(a) / 256.0;
+        double e2[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const double e = a[i] - mu;
+            e2[i] = e * e;
+        }
+        const double sigma = sqrt(block_pairwise_sum(e2) / 256.0);
+        double d64 = kTStar * sigma;
+        bool sat = false, zclamp = false;
+        if (d64 > 65504.0) { d64 = 65504.0; sat = true; }
+        const _Float16 dh = (_Float16)(float)d64;  // two roundings to nearest even, as specified
+        const double d = (double)dh;
+        const bool live = !row_bad && d > 0.0;  // otherwise the block is stored as zeros
+        const double rnd = floor(mu / (live ? d : 1.0) + 0.5);
+        double z = 0.0 - rnd;
+        if (z > 2048.0) { z = 2048.0; zclamp = true; }
+        if (z < -2048.0) { z = -2048.0; zclamp = true; }
+        const double t_hi = (0.5 - z) * d, t_lo = (-0.5 - z) * d;  // exact products
+        uint32_t word = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t c = a[i] >= t_hi ? 2u : (a[i] < t_lo ? 0u : 1u);
+            word |= c << (2 * i);
+        }
+        if (live) {
+            lo_word = word;
+            const _Float16 zh = (_Float16)(float)z;
+            scale_word = (uint32_t)__builtin_bit_cast(uint16_t, dh) | ((uint32_t)__builtin_bit_cast(uint16_t, zh) << 16);
+            if (zclamp) my_flags |= kFlagZClamp;
+        }
+        if (row_bad) my_flags |= kFlagNonFinite;
+        else if (sat) my_flags |= kFlagScaleSat;
     }
-    __syncthreads();
-    uint32_t* out = codes + tile * kTileWords;
-    out[threadIdx.x] = tile_lds[threadIdx.x];
-    if (threadIdx.x < kTileWords - 256) out[256 + threadIdx.x] = tile_lds[256 + threadIdx.x];
-    if (threadIdx.x < kTileRows) scales[tile * kTileRows + threadIdx.x] = scale_lds[threadIdx.x];
-    if (flags != nullptr && my_flags != 0u && lane == 0) atomicOr(flags, my_flags);
+    // elements 16 l16 .. 16 l16 + 15 of row r: low-plane word 4*(16*(l16>>2) + r) + (l16&3)
+    out[4 * (16 * (l16 >> 2) + r) + (l16 & 3)] = lo_word;
+    if (l16 == 0) scales[(int64_t)tile * kTileRows + r] = scale_word;
+    if (flags != nullptr && __builtin_amdgcn_ballot_w64(my_flags != 0u) != 0ull) {
+        // one atomic per wavefront: OR of the flags of its lanes
+        uint32_t f = my_flags;
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) f |= (uint32_t)__shfl_xor((int)f, m, 64);
+        if (lane == 0) atomicOr(flags, f);
+    }
 }
 
 int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* flags,
                     hipStream_t stream) {
     const int64_t tiles = ((N + 15) / 16) * (K / kBlock);
-    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, W, N, K, ldw, codes, scales, flags);
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)tiles), dim3(256), 0, stream, W, N, K, ldw, codes, scales, flags, (int)(K / kBlock));
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
