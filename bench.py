@@ -84,7 +84,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
     ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
-    ap.add_argument("--legs", default="per_shape,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
+    ap.add_argument("--legs", default="per_shape,stream70b,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -235,6 +235,8 @@ def main():
         out["prefill"] = prefill_leg(torch, binding, synth, gen)
     if "dequantize" in legs:
         out["dequantize"] = dequantize_leg(torch, binding, tensors)
+    if "stream70b" in legs and args.workload != "llama70b_decode":
+        out["stream70b"] = stream70b_leg(torch, binding, synth, gen)
     if "copy" in legs:
         out["copy_ceiling"] = copy_leg(torch)
     if "cpu" in legs:
@@ -337,6 +339,35 @@ def dequantize_leg(torch, binding, tensors):
     nbytes = packed_bytes(N, K) + N * K * 4
     return {"N": N, "K": K, "us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "output_buffers": nout}
+
+
+def stream70b_leg(torch, binding, synth, gen, n_layers=8):
+    """The 70B-shaped decode stream (M = 1) on a bounded number of layers (2.7 GB of packed weights
+    for 8 layers, still far beyond the last-level cache): one grouped call per stage, replayed graph."""
+    M = 1
+    stages = synth.LLAMA70B_STAGES
+    calls, nbytes = [], 0
+    xs = {K: activations(torch, gen, M, K) for K in sorted({st[0][2] for st in stages})}
+    ys = {name: torch.empty((M, N), dtype=torch.float16, device="cuda") for st in stages for name, N, K in st}
+    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for st in stages for _, N, K in st), dtype=torch.uint8, device="cuda")
+    for li in range(n_layers):
+        for st in stages:
+            wts = []
+            for name, N, K in st:
+                W = student_t_weights(torch, gen, N, K)
+                codes, scales = binding.itq3s_quantize(W)
+                del W
+                wts.append((codes, scales, N))
+                nbytes += packed_bytes(N, K)
+            calls.append((st[0][2], wts, [ys[name] for name, _, _ in st]))
+
+    def step():
+        for K, wts, outs in calls:
+            binding.itq3s_matmul_grouped(wts, K, xs[K], outs=outs, workspace=ws)
+
+    ms = graph_time(torch, step, 1, reps=20)
+    return {"workload": "llama70b_decode shapes, %d of 80 layers, M=1, fp16 out, %d grouped calls, %.2f GB packed" % (n_layers, len(calls), nbytes / 1e9),
+            "ms_per_step": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
 
 
 def copy_leg(torch):

@@ -48,14 +48,15 @@ LaunchTiming take_launch_timing() {
 }
 
 // One launch serves up to kGemvMaxGroup weight tensors that share K and the activations (the
-// projections of one layer that read the same input): tensor t owns the workgroups from wg_begin on.
+// projections of one layer that read the same input).  Their 16-row tiles are numbered as one list,
+// tensor after tensor, and split evenly over the workgroups; a workgroup's tiles may belong to two
+// tensors.
 struct GemvTensor {
     const uint32_t* codes;
     const uint32_t* scales;
     void* Y;
     int64_t N, ldy;
-    int wg_begin;    // first workgroup of this tensor (0x7fffffff for unused entries)
-    int nt_q, nt_r;  // row tiles per workgroup: the first nt_r workgroups own nt_q + 1, the others nt_q
+    int v_begin;  // position of this tensor's first row tile in the list (0x7fffffff for unused entries)
     int pad_;
 };
 
@@ -66,6 +67,7 @@ struct GemvArgs {
     uint32_t* flags;
     int64_t ldx;
     int KB, M, y_f16;
+    int nt_q, nt_r;  // row tiles per workgroup: the first nt_r workgroups own nt_q + 1, the others nt_q
 };
 
 struct TileRegs {
@@ -188,17 +190,48 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // wave-uniform, in an SGPR
     const int g = lane >> 4, r16 = lane & 15, mm = r16 & (MP - 1);
-    // which tensor (scalar selects over the few entries, all read with the first argument fetch),
-    // then 1..RT row tiles of it; no division and no dependent fetch on the way to the first load
-    GemvTensor T = a.t[0];
-    if constexpr (kGrouped) {
+    // 1..RT row tiles of the list (the host picks the grid that way); no division and no dependent
+    // fetch on the way to the first load.  Per slot: the tile row's first tile in codes / scales; a
+    // missing slot reads the first tile of the launch (never used).
+    const int wg = (int)blockIdx.x;
+    const int nt_begin = wg * a.nt_q + (wg < a.nt_r ? wg : a.nt_r);
+    const int cnt = a.nt_q + (wg < a.nt_r ? 1 : 0);
+    struct SlotOut {   // where the 16 outputs of a slot go (table in LDS, read back in the epilogue)
+        void* Y;
+        int64_t ldy;
+        int64_t n0;    // first row of the tile inside its tensor
+        int64_t rows;  // rows of that tensor from n0 on that exist (<= 0: slot unused)
+    };
+    SlotOut* const slot_out = reinterpret_cast<SlotOut*>(smem + (size_t)W * NBX * MP * (512 + 4) + (size_t)W * RT * MP * 16 * 4);
+    const uint32_t* slot_codes[RT];
+    const uint32_t* slot_scales[RT];
 #pragma unroll
-        for (int i = 1; i < kGemvMaxGroup; ++i)
-            if ((int)blockIdx.x >= a.t[i].wg_begin) T = a.t[i];
+    for (int rt = 0; rt < RT; ++rt) {
+        // tensor that owns list position nt_begin + rt (scalar selects; all descriptors come with the
+        // first argument fetch)
+        const uint32_t* t_codes = a.t[0].codes;
+        const uint32_t* t_scales = a.t[0].scales;
+        void* t_y = a.t[0].Y;
+        int64_t t_n = a.t[0].N, t_ldy = a.t[0].ldy;
+        int t_begin = 0;
+        if constexpr (kGrouped) {
+#pragma unroll
+            for (int i = 1; i < kGemvMaxGroup; ++i) {
+                const bool ge = nt_begin + rt >= a.t[i].v_begin;
+                t_codes = ge ? a.t[i].codes : t_codes;
+                t_scales = ge ? a.t[i].scales : t_scales;
+                t_y = ge ? a.t[i].Y : t_y;
+                t_n = ge ? a.t[i].N : t_n;
+                t_ldy = ge ? a.t[i].ldy : t_ldy;
+                t_begin = ge ? a.t[i].v_begin : t_begin;
+            }
+        }
+        const int64_t local = nt_begin + rt - t_begin;
+        const int64_t first = rt < cnt ? local * KB : 0;
+        slot_codes[rt] = (rt < cnt ? t_codes : a.t[0].codes) + first * kTileWords;
+        slot_scales[rt] = (rt < cnt ? t_scales : a.t[0].scales) + first * kTileRows;
+        if (threadIdx.x == 0) slot_out[rt] = SlotOut{t_y, t_ldy, local * 16, rt < cnt ? t_n - local * 16 : 0};
     }
-    const int wg = (int)blockIdx.x - T.wg_begin;
-    const int nt_begin = wg * T.nt_q + (wg < T.nt_r ? wg : T.nt_r);
-    const int cnt = T.nt_q + (wg < T.nt_r ? 1 : 0);
     const int nb = KB > wave ? (KB - wave + W - 1) / W : 0;  // blocks of this wavefront: b = wave + j*W
 
     // LDS: kFused: per wavefront NBX*MP*256 halves of x~, then NBX*MP sums per wavefront; then the
@@ -224,10 +257,8 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     auto issue = [&](Slot& s, int j) {
         const bool live = j < nb;
         const int b = wave + j * W;
-        const int64_t t0 = live ? (int64_t)nt_begin * KB + b : 0;
-        const int64_t step = live ? KB : 0;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) load_tile(s.t[rt], T.codes, T.scales, rt < cnt ? t0 + rt * step : 0, lane);
+        for (int rt = 0; rt < RT; ++rt) load_tile(s.t[rt], slot_codes[rt], slot_scales[rt], live ? b : 0, lane);
         if constexpr (!kFused) {
             const int bb = live ? b : 0;
 #pragma unroll
@@ -319,7 +350,8 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         compute(ring[k % NB], bi + k);
     }
 
-    // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]
+    // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]; slot_out says where
+    // the 16 outputs of a slot go
     __syncthreads();
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
@@ -329,14 +361,15 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     __syncthreads();
     for (int o = threadIdx.x; o < RT * 16 * MP; o += W * 64) {
         const int rr = o % (RT * 16), m = o / (RT * 16);  // rr = rt*16 + r: consecutive threads, consecutive n
-        const int rt = rr >> 4;
-        const int64_t n = (int64_t)nt_begin * 16 + rr;
-        if (rt < cnt && n < T.N && m < a.M) {
+        const int rt = rr >> 4, r = rr & 15;
+        const SlotOut so = slot_out[rt];
+        if (r < so.rows && m < a.M) {
             float sum = 0.f;
 #pragma unroll
-            for (int wv = 0; wv < W; ++wv) sum += red[((wv * RT + rt) * MP + m) * 16 + (rr & 15)];
-            if (a.y_f16) reinterpret_cast<_Float16*>(T.Y)[m * T.ldy + n] = (_Float16)sum;
-            else reinterpret_cast<float*>(T.Y)[m * T.ldy + n] = sum;
+            for (int wv = 0; wv < W; ++wv) sum += red[((wv * RT + rt) * MP + m) * 16 + r];
+            const int64_t n = so.n0 + r;
+            if (a.y_f16) reinterpret_cast<_Float16*>(so.Y)[m * so.ldy + n] = (_Float16)sum;
+            else reinterpret_cast<float*>(so.Y)[m * so.ldy + n] = sum;
         }
     }
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
@@ -350,7 +383,7 @@ static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
         lds_limit_raised = true;
     }
-    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 4) + (size_t)kGemvWaves * RT * MP * 16 * 4;
+    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 4) + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
@@ -359,7 +392,7 @@ static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
 
 template <int MP, int RT, int D, int NBX>
 static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
-    if (a.t[1].wg_begin != 0x7fffffff) return launch_kernel<MP, RT, D, NBX, true>(a, grid, stream);
+    if (a.t[1].v_begin != 0x7fffffff) return launch_kernel<MP, RT, D, NBX, true>(a, grid, stream);
     return launch_kernel<MP, RT, D, NBX, false>(a, grid, stream);
 }
 
@@ -441,55 +474,31 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
     if (count < 1 || count > kGemvMaxGroup) return -2;
     GemvArgs a;
     a.X = X; a.S = S; a.flags = flags; a.ldx = ldx; a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
-    // One workgroup per CU over all tensors if that leaves at most kGemvMaxRT row tiles each, else
-    // more workgroups.  (The kernel's registers allow one workgroup per CU at a time, so a grid just
-    // above the CU count would run a nearly empty second round.)  Every tensor gets its own
-    // workgroups; the split is greedy: the next workgroup goes to the tensor with the most row tiles
-    // per workgroup.
-    int64_t nt[kGemvMaxGroup] = {0, 0, 0, 0}, wgs[kGemvMaxGroup] = {0, 0, 0, 0}, nt_total = 0;
-    for (int i = 0; i < count; ++i) {
-        nt[i] = (w[i].N + 15) / 16;
-        nt_total += nt[i];
-    }
-    int64_t target = nt_total < cu_count() ? nt_total : cu_count();
-    if ((nt_total + target - 1) / target > kGemvMaxRT) target = (nt_total + kGemvMaxRT - 1) / kGemvMaxRT;
-    if (target < count) target = count;
-    int64_t given = 0;
-    for (int i = 0; i < count; ++i) {  // proportional share, rounded down, at least one
-        wgs[i] = nt[i] * target / nt_total;
-        if (wgs[i] < 1) wgs[i] = 1;
-        given += wgs[i];
-    }
-    for (; given < target; ++given) {
-        int best = 0;
-        for (int i = 1; i < count; ++i)
-            if (nt[i] * wgs[best] > nt[best] * wgs[i]) best = i;  // nt[i]/wgs[i] > nt[best]/wgs[best]
-        ++wgs[best];
-    }
-    int rt = 1;
-    for (int i = 0; i < count; ++i) {
-        if ((nt[i] + wgs[i] - 1) / wgs[i] > kGemvMaxRT) wgs[i] = (nt[i] + kGemvMaxRT - 1) / kGemvMaxRT;
-        if (wgs[i] > nt[i]) wgs[i] = nt[i];
-        const int r = (int)((nt[i] + wgs[i] - 1) / wgs[i]);
-        if (r > rt) rt = r;
-    }
-    int64_t grid64 = 0;
+    // One workgroup per CU if that leaves at most kGemvMaxRT row tiles each, else more workgroups.
+    // (The kernel's registers allow one workgroup per CU at a time, so a grid just above the CU count
+    // would run a nearly empty second round.)  The row tiles of all tensors form one list, split
+    // evenly: every workgroup gets rt or rt-1 of them.
+    int64_t nt_total = 0;
     for (int i = 0; i < kGemvMaxGroup; ++i) {
         GemvTensor& t = a.t[i];
         if (i < count) {
             t.codes = w[i].codes; t.scales = w[i].scales; t.Y = w[i].Y; t.N = w[i].N; t.ldy = w[i].ldy;
-            t.wg_begin = (int)grid64;
-            t.nt_q = (int)(nt[i] / wgs[i]);
-            t.nt_r = (int)(nt[i] % wgs[i]);
-            grid64 += wgs[i];
+            if (nt_total > 0x7fffffff) return -2;
+            t.v_begin = (int)nt_total;
+            nt_total += (w[i].N + 15) / 16;
         } else {
             t = a.t[0];
-            t.wg_begin = 0x7fffffff;
+            t.v_begin = 0x7fffffff;
         }
         t.pad_ = 0;
     }
-    if (grid64 > 0x7fffffff) return -2;
+    if (nt_total >= 0x7fffffff) return -2;
+    int64_t grid64 = nt_total < cu_count() ? nt_total : cu_count();
+    if ((nt_total + grid64 - 1) / grid64 > kGemvMaxRT) grid64 = (nt_total + kGemvMaxRT - 1) / kGemvMaxRT;
     const int grid = (int)grid64;
+    const int rt = (int)((nt_total + grid - 1) / grid);
+    a.nt_q = (int)(nt_total / grid);
+    a.nt_r = (int)(nt_total % grid);
     const int nb_min = a.KB / kGemvWaves, nb_max = (a.KB + kGemvWaves - 1) / kGemvWaves;
     if (fused) {
         switch (MP) {
