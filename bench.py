@@ -1,19 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the ITQ3_S hot path on one MI355X.
 
-A step is one decode pass (M = 1) over every weight tensor of a transformer-shaped stack: for each
-tensor one itq3s_matmul call (activation rotation + streaming contraction + epilogue) on packed
-weights that are resident in HBM.  The default workload is the Llama-7B-shaped configuration
+A step is one decode pass (M = 1) over every weight tensor of a transformer-shaped stack, in the
+order of the layer's data flow: q, k, v (same input) -> o -> gate, up (same input) -> down.  Tensors
+that read the same activations go into one itq3s_matmul_grouped call (one launch: activation
+rotation + streaming contraction + epilogue); `--ungrouped` issues one itq3s_matmul per tensor.
+All packed weights are resident in HBM.  The default workload is the Llama-7B-shaped configuration
 (32 layers x {4 x 4096x4096, 2 x 11008x4096, 1 x 4096x11008}, 2.5 GB packed, so that no tensor is
-re-read from a cache); `--workload llama70b_decode` runs the 80-layer 70B-shaped stream (26.7 GB).
-Weights are synthetic (Student-t, see paper_2603_27914_amd/synth.py), generated on the device and
-packed by itq3s_quantize, which is timed as well.
+re-read from a cache); `--workload llama70b_decode` runs the 80-layer 70B-shaped stream (26.7 GB),
+of which the default run times 8 layers as an extra leg.  Weights are synthetic (Student-t, see
+paper_2603_27914_amd/synth.py), generated on the device and packed by itq3s_quantize, which is
+timed as well.
 
 Prints ONE JSON line.  `value` = packed-weight bytes streamed per second over the whole step
 (wall clock over the replayed graph, launch gaps included).  `roofline` prices the streaming
 contraction kernel alone: algorithmic bytes of a call over the kernel's own duration, which
-itq3s_matmul_timed reads from HIP events attached to the kernel's dispatch, averaged over one more
-pass through every tensor of the step (the same quantity rocprofv3 --kernel-trace --stats lists as
+itq3s_matmul_grouped_timed reads from HIP events attached to the kernel's dispatch, averaged over
+one more pass through every call of the step (the same quantity rocprofv3 --kernel-trace --stats lists as
 the kernel's average duration).
 """
 import argparse
@@ -34,10 +37,11 @@ MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 # rocprofv3 --pmc passes over this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
 # counter shows for copy_leg's 1 GiB copy; the summaries and the commands are under profiles/.
 MEASURED_TRAFFIC = {
-    # (128 x 6608.9 + 64 x 17456.4 + 32 x 17551.9) / 224 KiB fetched, (128 x 16 + 64 x 43 + 32 x 16) / 224 KiB
-    # written, against 11,327,707 algorithmic bytes: 2 % of re-reads (activations and stand-in loads)
-    "llama7b_decode": {"bytes_per_launch": 11566270, "fetch_bytes": 11541987, "write_bytes": 24283,
-                       "source": "profiles/gemv_llama7b_decode.hbm_traffic.txt"},
+    # per launch of the grouped step: fetched (19427.7 + 6570.9 + 34888.5 + 17588.1) / 4 KiB, written
+    # (48 + 16 + 86 + 16) / 4 KiB, against 19,823,488 algorithmic bytes: 1.6 % of re-reads (the
+    # activations, read by every workgroup, and stand-in loads)
+    "llama7b_decode": {"bytes_per_launch": 20132147, "fetch_bytes": 20089651, "write_bytes": 42496,
+                       "source": "profiles/gemv_quantize_llama7b_decode.hbm_traffic.txt"},
 }
 
 WORKLOADS = {
