@@ -22,7 +22,8 @@ WorkspacePlan plan_workspace(int64_t M, int64_t K) {
     WorkspacePlan p;
     const int64_t rows = M <= itq3s::kGemvMaxM ? pad_m(M) : M;
     p.xt_bytes = round_up((size_t)rows * (size_t)K * 2, 256);
-    p.s_bytes = M <= itq3s::kGemvMaxM ? round_up((size_t)rows * (size_t)(K / 256) * 4, 256) : 0;
+    // streaming path without in-kernel rotation: two sums per (block, row), see launch_rotate_frag
+    p.s_bytes = M <= itq3s::kGemvMaxM ? round_up((size_t)rows * (size_t)(K / 256) * 8, 256) : 0;
     p.total = p.xt_bytes + p.s_bytes + 256;
     return p;
 }
@@ -103,7 +104,7 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
     }
     // tiled path: one rotation, then one contraction launch per tensor
     int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, st);
-    for (int i = 0; i < count && rc == 0; ++i) rc = itq3s::launch_gemm(w[i].codes, w[i].scales, w[i].N, K, Xt, M, w[i].Y, y_f16, w[i].ldy, status_flags, st);
+    for (int i = 0; i < count && rc == 0; ++i) rc = itq3s::launch_gemm(w[i].codes, w[i].scales, w[i].N, K, Xt, Xh, ldx, M, w[i].Y, y_f16, w[i].ldy, status_flags, st);
     return rc;
 }
 

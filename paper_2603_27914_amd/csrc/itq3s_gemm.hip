@@ -4,7 +4,13 @@
 // rotation having been moved to the activations (Sec. 2.3: <H v, x> = <v, H x>), so the tile loader
 // needs two packed-fp16 operations per pair of weights and no butterflies.
 //
-//   Y[m][n] = sum_k x~[m][k'] * g[n][k'],   g = d (c - 1 - z)
+//   Y[m][n] = sum_k x~[m][k'] * g[n][k']  -  sum_b d z 16 x[m][256 b],   g = d (c - 1)  (exact in fp16)
+//
+// The zero-point multiplies the sum of the rotated chunk, and H 1 = 16 e_0 makes that sum exactly
+// 16 times the chunk's first element: the term is formed from the activations themselves in fp32.
+// Folding z into the fp16 operand instead would multiply the rounding errors of x~ by z.  The term
+// is rare (a fraction of a percent of the blocks on real weights), so the kernels note while they run
+// whether a zero-point came by and only then walk the scale words of their columns at the end.
 //
 // k' is the channel order the unpack produces (within each group of 16 channels: 0,8,1,9,...,7,15);
 // the rotation kernel writes x~ in the same order, so both LDS tiles are plain [row][k'].
@@ -31,11 +37,43 @@ struct GemmArgs {
     const uint32_t* codes;
     const uint32_t* scales;
     const _Float16* Xt;  // [M][K] in k' order
+    const _Float16* X;   // [M][ldx] the activations themselves (zero-point term)
     void* Y;
     uint32_t* flags;
-    int64_t N, K, M, ldy;
+    int64_t N, K, M, ldy, ldx;
     int NT, KB, y_f16;
 };
+
+// Zero-point term of one 32 x 32 output block that has already been stored: column n (this lane's),
+// rows row0 + 8*(v/4) + 4*kg + v%4.  Walks the column's scale words and, for blocks with z != 0,
+// subtracts d z 16 x[m][256 b] from the stored outputs (each output belongs to one lane).  Working
+// on memory keeps the rare path out of the register budget of the main loop.
+__device__ __forceinline__ void subtract_zero_points(const GemmArgs& a, int64_t n, int64_t row0, int kg) {
+    if (n >= a.N) return;
+    const uint32_t* sc = a.scales + (n >> 4) * a.KB * kTileRows + (n & 15);
+#pragma unroll 1
+    for (int b = 0; b < a.KB; ++b) {
+        const uint32_t w = sc[(int64_t)b * kTileRows];
+        const float z = f16_bits_to_f32(w >> 16);
+        if (z != 0.f) {
+            const float dz = f16_bits_to_f32(w & 0xffffu) * z;
+#pragma unroll 1
+            for (int v = 0; v < 16; ++v) {
+                const int64_t m = row0 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                if (m < a.M) {
+                    const float t = dz * (16.0f * (float)a.X[m * a.ldx + (int64_t)b * kBlock]);
+                    if (a.y_f16) {
+                        _Float16* y = reinterpret_cast<_Float16*>(a.Y) + m * a.ldy + n;
+                        *y = (_Float16)((float)*y - t);
+                    } else {
+                        float* y = reinterpret_cast<float*>(a.Y) + m * a.ldy + n;
+                        *y = *y - t;
+                    }
+                }
+            }
+        }
+    }
+}
 
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
     __shared__ __align__(16) _Float16 As[BM * LDT];
@@ -53,7 +91,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
     // activation loader role: four 16-byte pieces per thread
     uint4 xa[4];
     uint2 wlo;
-    uint32_t whi = 0, wsc = 0, bad = 0;
+    uint32_t whi = 0, wsc = 0, bad = 0, any_z = 0;
 
     auto load_global = [&](int kt) {
         const int b = kt >> 2, q = kt & 3;
@@ -84,13 +122,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
             *reinterpret_cast<uint4*>(&As[row * LDT + c16 * 8]) = xa[i];
         }
         bad |= whi;
-        // g = d * (c - 1 - z): c * 2^-14 sits in bits 11:10 of each half after shift-and-mask
+        any_z |= (wsc >> 16) & 0x7fffu;
+        // g = d * (c - 1): c * 2^-14 sits in bits 11:10 of each half after shift-and-mask
         const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(wsc & 0xffffu));
-        const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)(wsc >> 16));
         const half2v dd = {d, d};
         const half2v k14 = {(_Float16)16384.0f, (_Float16)16384.0f};
-        const _Float16 off1 = (_Float16)(-1.0f) - z;
-        const half2v off = {off1, off1};
+        const half2v off = {(_Float16)(-1.0f), (_Float16)(-1.0f)};
         const uint32_t w2[2] = {wlo.x, wlo.y};
         _Float16* dst = &Bs[(wtl * 16 + wr) * LDT + 32 * wp];
 #pragma unroll
@@ -153,6 +190,14 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
                 }
             }
         }
+    // zero-point term, only if some block of the workgroup's 128 rows has one
+    if (__syncthreads_or(any_z != 0u)) {
+#pragma unroll 1
+        for (int ij = 0; ij < 4; ++ij) {
+            const int i = ij >> 1, j = ij & 1;
+            subtract_zero_points(a, (int64_t)nt0 * 16 + wn * 64 + j * 32 + l32, m0 + wm * 64 + i * 32, kg);
+        }
+    }
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
@@ -166,7 +211,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 // channels k' of the step -- and one low-plane word of the packed tile holds exactly the 16 channels
 // of one step of one row, in k' order after the shift-and-mask unpack (pairs (slot j, slot j+8)).
 // So every lane loads the words of its own two rows (16 bytes = four steps per load), turns its
-// half of a word into four half2 values d (c - 1 - z) in registers, and feeds the matrix core.  The
+// half of a word into four half2 values d (c - 1) in registers, and feeds the matrix core.  The
 // two wavefronts that share a column range repeat that unpack; in exchange the LDS carries half the
 // traffic and the weight path needs no barrier.
 //
@@ -248,16 +293,16 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
         }
     };
     // Unpack: a code OR-ed into the mantissa of 1024.0 (bit pattern 0x6400, unit in the last place 1)
-    // is the half 1024 + c; adding -(1025 + z) gives c - 1 - z exactly (for |1025 + z| <= 2048; beyond
-    // that the constant rounds to an even integer, an error of 1 in 2000), times d.
-    half2v dd[2], off[2];  // per row: d and -(1025 + z) of the block being unpacked
+    // is the half 1024 + c; adding -1025 gives the digit c - 1 exactly, times d (exact).
+    half2v dd[2];  // per row: d of the block being unpacked
+    const half2v off = {(_Float16)(-1025.0f), (_Float16)(-1025.0f)};
+    uint32_t any_z = 0;  // did one of this lane's rows see a zero-point?
     auto set_scale = [&](const uint32_t (&sc)[2]) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(sc[j] & 0xffffu));
-            const _Float16 o = (_Float16)(-1025.0f - (float)__builtin_bit_cast(_Float16, (uint16_t)(sc[j] >> 16)));
             dd[j] = half2v{d, d};
-            off[j] = half2v{o, o};
+            any_z |= (sc[j] >> 16) & 0x7fffu;
         }
     };
     // word = the 16 channels of one MFMA step of row j; this lane's eight are the pairs 4kg .. 4kg+3
@@ -267,7 +312,7 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             half2v h = __builtin_bit_cast(half2v, ((v >> (2 * p)) & 0x00030003u) | 0x64006400u);
-            h = (h + off[j]) * dd[j];
+            h = (h + off) * dd[j];
             o[p] = __builtin_bit_cast(uint32_t, h);
         }
         const uint4 u = make_uint4(o[0], o[1], o[2], o[3]);
@@ -372,13 +417,22 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
                 }
             }
         }
+    // zero-point term, only if a lane of this wavefront met one (columns past N read clamped rows and
+    // may trigger it needlessly; nothing is stored for them)
+    if (__builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull) {
+#pragma unroll 1
+        for (int ij = 0; ij < 8; ++ij) {
+            const int i = ij >> 1, j = ij & 1;
+            subtract_zero_points(a, n0 + wn * 64 + j * 32 + l32, m0 + wm * 128 + i * 32, kg);
+        }
+    }
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
-int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
-                int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
+int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const _Float16* X, int64_t ldx,
+                int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
     GemmArgs a;
-    a.codes = codes; a.scales = scales; a.Xt = Xt; a.Y = Y; a.flags = flags;
+    a.codes = codes; a.scales = scales; a.Xt = Xt; a.X = X; a.ldx = ldx; a.Y = Y; a.flags = flags;
     a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
     const LaunchTiming tm = take_launch_timing();
     const int64_t tiles_m = (M + GM - 1) / GM, tiles_n = (N + GN - 1) / GN;

@@ -1,9 +1,12 @@
 // Streaming matmul for M <= 16 activation rows (the decode path, Sec. 5.4).
 //
-//   Y[m][n] = sum_b d[n,b] * ( sum_j c[n,b,j] x~[m,b,j]  -  (1 + z[n,b]) * S[m,b] )
+//   Y[m][n] = sum_b d[n,b] * ( sum_j c[n,b,j] x~[m,b,j]  -  S[m,b]  -  z[n,b] * E[m,b] )
 //
-// with c = q+1 the stored code, x~ = H x the rotated activation chunk and S[m,b] = sum_j x~[m,b,j]
-// (so that sum_j (c-1-z) x~ is formed without ever touching a signed digit).  The packed weights are
+// with c = q+1 the stored code, x~ = H x the rotated activation chunk rounded to fp16,
+// S[m,b] = sum_j x~[m,b,j] over those rounded values (it cancels the +1 of the codes exactly, so that
+// sum_j (c-1) x~ is formed without ever touching a signed digit) and E[m,b] = 16 x[m, 256 b], the
+// exact value of the same sum before rounding (H 1 = 16 e_0): the zero-point term is formed from
+// the activations themselves, so the rounding of x~ is not multiplied by z.  The packed weights are
 // read exactly once, with one 16-byte + one 8-byte + one 4-byte (scale) load per lane and tile;
 // nothing dequantized is written anywhere.
 //
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         int64_t n0;    // first row of the tile inside its tensor
         int64_t rows;  // rows of that tensor from n0 on that exist (<= 0: slot unused)
     };
-    SlotOut* const slot_out = reinterpret_cast<SlotOut*>(smem + (size_t)W * NBX * MP * (512 + 4) + (size_t)W * RT * MP * 16 * 4);
+    SlotOut* const slot_out = reinterpret_cast<SlotOut*>(smem + (size_t)W * NBX * MP * (512 + 8) + (size_t)W * RT * MP * 16 * 4);
     const uint32_t* slot_codes[RT];
     const uint32_t* slot_scales[RT];
 #pragma unroll
@@ -234,11 +237,12 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     }
     const int nb = KB > wave ? (KB - wave + W - 1) / W : 0;  // blocks of this wavefront: b = wave + j*W
 
-    // LDS: kFused: per wavefront NBX*MP*256 halves of x~, then NBX*MP sums per wavefront; then the
-    // reduction buffer
+    // LDS: kFused: per wavefront NBX*MP*256 halves of x~, then per wavefront NBX*MP sums S and NBX*MP
+    // sums E; then the reduction buffer
     _Float16* xs = reinterpret_cast<_Float16*>(smem) + (size_t)wave * NBX * MP * 256;
-    float* ss = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * 512) + wave * NBX * MP;
-    float* red = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * (512 + 4));  // W*RT*MP*16 floats
+    float* ss = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * 512) + wave * NBX * MP * 2;
+    float* se = ss + NBX * MP;
+    float* red = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * (512 + 8));  // W*RT*MP*16 floats
 
     floatx4 acc[RT];
 #pragma unroll
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     struct Slot {
         TileRegs t[RT];
         half8 xf[kFused ? 1 : 8];
-        floatx4 sv;
+        floatx4 sv, ev;
     };
     Slot ring[NB];
 
@@ -263,28 +267,37 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
             const int bb = live ? b : 0;
 #pragma unroll
             for (int t = 0; t < 8; ++t) s.xf[t] = *reinterpret_cast<const half8*>(a.X + ((size_t)((bb * 8 + t) * 4 + g) * MP + mm) * 8);
+            const float* E = a.S + (size_t)KB * MP;
             if constexpr (MP >= 4) {
                 s.sv = *reinterpret_cast<const floatx4*>(a.S + (size_t)bb * MP + ((4 * g) & (MP - 1)));
+                s.ev = *reinterpret_cast<const floatx4*>(E + (size_t)bb * MP + ((4 * g) & (MP - 1)));
             } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) s.sv[i] = a.S[(size_t)bb * MP + ((4 * g + i) & (MP - 1))];
+                for (int i = 0; i < 4; ++i) {
+                    s.sv[i] = a.S[(size_t)bb * MP + ((4 * g + i) & (MP - 1))];
+                    s.ev[i] = E[(size_t)bb * MP + ((4 * g + i) & (MP - 1))];
+                }
             }
         }
     };
 
     auto compute = [&](const Slot& s, int j) {
         half8 Xf[8];
-        floatx4 sv;
+        floatx4 sv, ev;
         if constexpr (kFused) {
             const _Float16* xb = xs + (size_t)j * MP * 256;
 #pragma unroll
             for (int t = 0; t < 8; ++t) Xf[t] = *reinterpret_cast<const half8*>(xb + ((t * 4 + g) * MP + mm) * 8);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
+            for (int i = 0; i < 4; ++i) {
+                sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
+                ev[i] = se[j * MP + ((4 * g + i) & (MP - 1))];
+            }
         } else {
 #pragma unroll
             for (int t = 0; t < 8; ++t) Xf[t] = s.xf[t];
             sv = s.sv;
+            ev = s.ev;
         }
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -293,9 +306,10 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
                 const floatx4 c = tile_dot(tr.lo, Xf);
                 bad |= tr.hi.x | tr.hi.y;
                 const float d = f16_bits_to_f32(tr.sc & 0xffffu);
-                const float z1 = 1.0f + f16_bits_to_f32(tr.sc >> 16);
+                const float z = f16_bits_to_f32(tr.sc >> 16);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) acc[rt][i] = __builtin_fmaf(d, __builtin_fmaf(c[i], 16384.0f, -(z1 * sv[i])), acc[rt][i]);
+                for (int i = 0; i < 4; ++i)
+                    acc[rt][i] = __builtin_fmaf(d, __builtin_fmaf(c[i], 16384.0f, -__builtin_fmaf(z, ev[i], sv[i])), acc[rt][i]);
             }
         }
     };
@@ -328,7 +342,11 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
                 u32x2 raw = xraw[j * MP + m];
                 if (m >= a.M) raw = u32x2{0u, 0u};
                 const float s = rotate_to_lds<MP>(raw, H, lane, m, xs + (size_t)j * MP * 256);
-                if (lane == 0) ss[j * MP + m] = s;
+                if (lane == 0) {
+                    ss[j * MP + m] = s;
+                    // lane 0 holds x[0..3] of the chunk: E = 16 x_0
+                    se[j * MP + m] = 16.0f * (float)__builtin_bit_cast(_Float16, (uint16_t)(raw.x & 0xffffu));
+                }
             }
         }
     }
@@ -383,7 +401,7 @@ static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
         lds_limit_raised = true;
     }
-    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 4) + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
+    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 8) + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);

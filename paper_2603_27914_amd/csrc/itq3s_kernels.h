@@ -31,7 +31,8 @@ int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, 
                       uint32_t* flags, hipStream_t stream);
 
 // Rotated activations for the streaming path: Xt in MFMA operand order with MP (power of two >= M,
-// <= 16) columns, S[b*MP + m] = sum over the rounded rotated chunk.
+// <= 16) columns; S[b*MP + m] = sum over the rounded rotated chunk, S[KB*MP + b*MP + m] = the exact
+// sum of the unrounded one, 16 x[m][256 b].
 int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, hipStream_t stream);
 
 // Rotated activations for the tiled path: Xt[m][k] row-major, row stride K.
@@ -55,7 +56,8 @@ struct GemvWeight {
 int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
                 int y_f16, uint32_t* flags, hipStream_t stream);
 
-int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, int64_t M, void* Y,
-                int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+// Xt = rotated activations (launch_rotate_rowmajor); X, ldx = the activations themselves (zero-point term).
+int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const _Float16* X, int64_t ldx,
+                int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
 
 }  // namespace itq3s

@@ -46,7 +46,8 @@ __device__ __forceinline__ void rotate_chunk(const _Float16* __restrict__ src, i
 // (column m, k-group g) eight halves; position i of those eight is element
 //     e = 64 g + 16 (t>>1) + 4 (t&1) + (i>>1) + 8 (i&1)
 // of the chunk, which is where the weight kernel's shift-and-mask unpack puts the code of the same
-// element.  Xt index = (((b*8 + t)*4 + g)*MP + m)*8 + i.   S[b*MP + m] = sum_e x~_e (rounded values).
+// element.  Xt index = (((b*8 + t)*4 + g)*MP + m)*8 + i.   S[b*MP + m] = sum_e x~_e (rounded values),
+// S[KB*MP + b*MP + m] = 16 x_0 (the same sum before rounding, exact).
 __global__ __launch_bounds__(256) void rotate_frag_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx, int MP,
                                                           _Float16* __restrict__ Xt, float* __restrict__ S) {
     const int64_t KB = K / kBlock;
@@ -59,7 +60,11 @@ __global__ __launch_bounds__(256) void rotate_frag_kernel(const _Float16* __rest
     float s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
 #pragma unroll
     for (int k = 1; k < 64; k <<= 1) s += xor_lane_f32(s, k);
-    if (lane == 0) S[b * MP + m] = s;
+    if (lane == 0) {
+        S[b * MP + m] = s;
+        // exact sum of the unrounded chunk: H 1 = 16 e_0
+        S[KB * MP + b * MP + m] = m < M ? 16.0f * (float)X[m * ldx + b * kBlock] : 0.f;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int e = 64 * (lane >> 4) + 16 * j + (lane & 15);

@@ -337,6 +337,46 @@ def test_matmul_grouped_rejects_bad_arguments(gpu, ref):
         binding.itq3s_matmul_grouped([dev], K, X, workspace=small)
 
 
+@pytest.mark.parametrize("M", [1, 4, 16, 40, 300])
+def test_matmul_extreme_zero_points(gpu, ref, M):
+    """Zero-points over the whole stored range (+-2048), on every path: the streaming kernel applies
+    z in fp32, the tiled kernels in fp16 (exact up to |z| of about 1000, then within 1/2000)."""
+    torch, binding = gpu
+    N, K = 600, 1024
+    codes, scales = synth.random_packed(N, K, "bigz")
+    rng = np.random.default_rng(11)
+    z = np.zeros(scales.size, dtype=np.float16)
+    pick = rng.random(scales.size) < 0.05
+    z[pick] = rng.choice(np.array([-2048, -1500, -1024, -1023, -37, 5, 1022, 1023, 1024, 1500, 2047, 2048], dtype=np.float16), size=int(pick.sum()))
+    scales = (scales & np.uint32(0xffff)) | (z.view(np.uint16).astype(np.uint32) << np.uint32(16))
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    X = synth.activations(M, K, "bigz", M)
+    got = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X)).cpu().numpy()
+    want = ref.matmul(codes, scales, N, K, X)
+    assert rel_rows(got, want) <= MATMUL_TOL
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 4096, 512), (2000, 4100, 768)])
+def test_matmul_large_tile_kernel_ragged_and_zero_points(gpu, ref, M, N, K):
+    """Enough 256 x 256 tiles for the large-M kernel; ragged M and N; zero-points over the whole range;
+    checked on column spans (first, one that straddles a tile edge, last) for all rows."""
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "bigtile")
+    rng = np.random.default_rng(12)
+    z = np.zeros(scales.size, dtype=np.float16)
+    pick = rng.random(scales.size) < 0.02
+    z[pick] = rng.choice(np.array([-2048, -1024, -3, 2, 1023, 1024, 2048], dtype=np.float16), size=int(pick.sum()))
+    scales = (scales & np.uint32(0xffff)) | (z.view(np.uint16).astype(np.uint32) << np.uint32(16))
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    X = synth.activations(M, K, "bigtile", M)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), status_flags=flags).cpu().numpy()
+    assert int(flags.item()) == 0
+    for n0, n1 in [(0, 48), (240, 272), (N - 40, N)]:
+        want = ref.matmul(codes, scales, N, K, X, rows=(n0, n1))
+        assert rel_rows(got[:, n0:n1], want[:, n0:n1]) <= MATMUL_TOL
+
+
 def test_matmul_flags_high_plane(gpu, ref):
     torch, binding = gpu
     codes, scales = synth.random_packed(64, 512, "hp")
