@@ -377,6 +377,77 @@ def test_matmul_large_tile_kernel_ragged_and_zero_points(gpu, ref, M, N, K):
         assert rel_rows(got[:, n0:n1], want[:, n0:n1]) <= MATMUL_TOL
 
 
+def test_matmul_streaming_more_row_tiles_than_one_round(gpu, ref):
+    """N large enough that a workgroup per CU would need more than 7 row tiles: the grid grows beyond
+    the CU count (a second round); checked on spans at both ends and in the middle."""
+    torch, binding = gpu
+    N, K = 30000, 512
+    codes, scales = synth.random_packed(N, K, "tall")
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    for M in (1, 3, 16):
+        X = synth.activations(M, K, "tall", M)
+        got = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X)).cpu().numpy()
+        for n0, n1 in [(0, 300), (14990, 15300), (N - 300, N)]:
+            want = ref.matmul(codes, scales, N, K, X, rows=(n0, n1))
+            assert rel_rows(got[:, n0:n1], want[:, n0:n1]) <= MATMUL_TOL
+
+
+@pytest.mark.parametrize("scale", [1e-3, 1.0, 200.0])
+def test_matmul_activation_magnitudes(gpu, ref, scale):
+    """Activations from 1e-3 to several thousand (the rotation keeps its intermediate inside fp16 for
+    |x| up to 16376): same relative accuracy on the streaming and the tiled path."""
+    torch, binding = gpu
+    N, K = 512, 2048
+    codes, scales = synth.random_packed(N, K, "mag")
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    for M in (1, 4, 8, 48):
+        X = (synth.activations(M, K, "mag", M).astype(np.float32) * scale).astype(np.float16)
+        assert np.isfinite(X).all()
+        got = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X)).cpu().numpy()
+        want = ref.matmul(codes, scales, N, K, X)
+        assert np.isfinite(got).all()
+        assert rel_rows(got, want) <= MATMUL_TOL
+
+
+def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
+    """One workspace, calls of different shapes and paths enqueued back to back on one stream with no
+    host synchronisation in between: each result equals the one computed alone."""
+    torch, binding = gpu
+    cases = [(1, 1000, 11008), (8, 272, 4096), (40, 512, 1024), (3, 4096, 11008), (1, 2048, 2048)]
+    packed = {}
+    for M, N, K in cases:
+        c, s = synth.random_packed(N, K, "ws")
+        packed[(N, K)] = (to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)))
+    xs = [to_dev(torch, synth.activations(M, K, "ws", i)) for i, (M, N, K) in enumerate(cases)]
+    alone = [binding.itq3s_matmul(*packed[(N, K)], N, K, x) for (M, N, K), x in zip(cases, xs)]
+    torch.cuda.synchronize()
+    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for M, N, K in cases), dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        outs = [binding.itq3s_matmul(*packed[(N, K)], N, K, x, workspace=ws) for (M, N, K), x in zip(cases, xs)]
+        torch.cuda.synchronize()
+        for a, b in zip(alone, outs):
+            assert torch.equal(a, b)
+
+
+def test_matmul_grouped_flags_and_determinism(gpu, ref):
+    """The high-plane check covers every tensor of a grouped call; two identical calls give identical bits."""
+    torch, binding = gpu
+    K, Ns = 2048, [300, 4096, 48]
+    packed = [synth.random_packed(N, K, "grpflag", i) for i, N in enumerate(Ns)]
+    bad = packed[2][0].copy()
+    bad[(2 * (K // 256) + 1) * 384 + 256 + 7] |= np.uint32(1 << 9)  # a high-plane bit in the last tensor
+    X = to_dev(torch, synth.activations(2, K, "grpflag"))
+    for variant, expect in ((packed[2][0], 0), (bad, 8)):
+        dev = [(to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)), N) for (c, s), N in zip(packed[:2] + [(variant, packed[2][1])], Ns)]
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        a = binding.itq3s_matmul_grouped(dev, K, X, status_flags=flags)
+        b = binding.itq3s_matmul_grouped(dev, K, X)
+        torch.cuda.synchronize()
+        assert int(flags.item()) == expect
+        for u, v in zip(a, b):
+            assert torch.equal(u, v)
+
+
 def test_matmul_flags_high_plane(gpu, ref):
     torch, binding = gpu
     codes, scales = synth.random_packed(64, 512, "hp")
