@@ -88,7 +88,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
     ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
-    ap.add_argument("--legs", default="per_shape,stream70b,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
+    ap.add_argument("--legs", default="per_shape,read_floor,stream70b,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -241,6 +241,8 @@ def main():
         out["dequantize"] = dequantize_leg(torch, binding, tensors)
     if "stream70b" in legs and args.workload != "llama70b_decode":
         out["stream70b"] = stream70b_leg(torch, binding, synth, gen)
+    if "read_floor" in legs:
+        out["read_floor"] = read_floor_leg(torch, binding, tensors)
     if "copy" in legs:
         out["copy_ceiling"] = copy_leg(torch)
     if "cpu" in legs:
@@ -372,6 +374,28 @@ def stream70b_leg(torch, binding, synth, gen, n_layers=8):
     ms = graph_time(torch, step, 1, reps=20)
     return {"workload": "llama70b_decode shapes, %d of 80 layers, M=1, fp16 out, %d grouped calls, %.2f GB packed" % (n_layers, len(calls), nbytes / 1e9),
             "ms_per_step": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+
+def read_floor_leg(torch, binding, tensors):
+    """A plain read of the packed code arrays of every tensor shape of the step (the resident copies in
+    turn, replayed graph): what a launch costs that only moves the bytes."""
+    res = []
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    shapes = []
+    for t in tensors:
+        if (t[0], t[1]) not in shapes:
+            shapes.append((t[0], t[1]))
+    for N, K in shapes:
+        same = [t for t in tensors if (t[0], t[1]) == (N, K)]
+
+        def run():
+            for t in same:
+                binding.itq3s_read_probe(t[2], sink)
+
+        ms = graph_time(torch, run, len(same))
+        nbytes = same[0][2].numel() * 4
+        res.append({"N": N, "K": K, "bytes": nbytes, "us": round(ms * 1e3, 2), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)})
+    return res
 
 
 def copy_leg(torch):

@@ -134,6 +134,12 @@ int itq3s_matmul_grouped_timed(const itq3s_weight *w, int count, int64_t K, cons
                                int y_dtype, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
                                void *stream, float *kernel_ms);
 
+/* Measurement aid: a plain streaming read of `bytes` bytes (rounded down to a multiple of 16) of device
+ * memory at src (16-byte aligned), nothing else -- the time such a launch takes is the practical floor
+ * for a streaming matmul over the same bytes.  sink: one device uint32 (written only for one
+ * particular checksum of the data; present so that the reads cannot be optimised away). */
+int itq3s_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
 /* Static text for a status code.  Never NULL. */
 const char *itq3s_strerror(int status);
 

@@ -25,6 +25,7 @@ EXPORTS = [
     "itq3s_matmul_grouped",
     "itq3s_matmul_grouped_timed",
     "itq3s_matmul_timed",
+    "itq3s_read_probe",
     "itq3s_strerror",
     "itq3s_version",
 ]
@@ -71,6 +72,8 @@ def lib():
         L.itq3s_matmul_grouped_timed.argtypes = L.itq3s_matmul_grouped.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_matmul_timed.restype = ci
         L.itq3s_matmul_timed.argtypes = L.itq3s_matmul.argtypes + [ctypes.POINTER(ctypes.c_float)]
+        L.itq3s_read_probe.restype = ci
+        L.itq3s_read_probe.argtypes = [vp, sz, vp, vp]
         L.itq3s_strerror.restype = ctypes.c_char_p
         L.itq3s_strerror.argtypes = [ci]
         L.itq3s_version.restype = ci
@@ -146,6 +149,12 @@ def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_
         )
     )
     return out
+
+
+def itq3s_read_probe(buf, sink):
+    """Plain streaming read of a device tensor (measurement aid); sink: int32[1] device tensor."""
+    _need_cuda(buf, sink)
+    _check(lib().itq3s_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()))
 
 
 def itq3s_matmul_grouped_timed(weights, K, X, outs=None, dtype=torch.float32, workspace=None, status_flags=None):

@@ -330,13 +330,13 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
             }
         }
     }
-#pragma unroll
-    for (int d = 0; d < D; ++d) issue(ring[d], d);
     if constexpr (kFused) {
+        // The rotations are interleaved with the first D steps of tile loads: a wavefront that issues
+        // loads spends most of that time waiting for the address unit, and the rotation (a chain of
+        // dependent matrix, convert and LDS instructions) fills those waits instead of following them.
         HadamardOperand H;
         H.init(lane);
-#pragma unroll
-        for (int j = 0; j < NBX; ++j) {
+        auto rotate_slot = [&](int j) {
 #pragma unroll
             for (int m = 0; m < MP; ++m) {
                 u32x2 raw = xraw[j * MP + m];
@@ -348,7 +348,17 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
                     se[j * MP + m] = 16.0f * (float)__builtin_bit_cast(_Float16, (uint16_t)(raw.x & 0xffffu));
                 }
             }
+        };
+#pragma unroll
+        for (int d = 0; d < (D > NBX ? D : NBX); ++d) {
+            if (d < D) issue(ring[d], d);
+            __builtin_amdgcn_sched_barrier(0);
+            if (d < NBX) rotate_slot(d);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    } else {
+#pragma unroll
+        for (int d = 0; d < D; ++d) issue(ring[d], d);
     }
 
     // ---- steady state: NB steps per trip, every prefetch is a live step
