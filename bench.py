@@ -322,7 +322,13 @@ def prefill_leg(torch, binding, synth, gen):
             ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
             ms = time_calls(torch, lambda: binding.itq3s_matmul(codes, scales, N, K, X, out=Y, workspace=ws), 20)
             tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 1), "TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)})
+            _, kms = binding.itq3s_matmul_timed(codes, scales, N, K, X, out=Y, workspace=ws)
+            # the paper's placement of the transform (inside the weight tile loader), for comparison
+            binding.itq3s_matmul_weight_side(codes, scales, N, K, X, out=Y)
+            _, wms = binding.itq3s_matmul_weight_side(codes, scales, N, K, X, out=Y, timed=True)
+            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 1), "TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
+                        "kernel_us": round(kms * 1e3, 1), "kernel_TFLOPs": round(2.0 * M * N * K / (kms * 1e-3) / 1e12, 1),
+                        "weight_side_kernel_us": round(wms * 1e3, 1), "weight_side_TFLOPs": round(2.0 * M * N * K / (wms * 1e-3) / 1e12, 1)})
     return res
 
 

@@ -120,6 +120,18 @@ typedef struct itq3s_weight {
 int itq3s_matmul_grouped(const itq3s_weight *w, int count, int64_t K, const void *X, int64_t M, int64_t ldx, int y_dtype,
                          void *workspace, size_t workspace_bytes, uint32_t *status_flags, void *stream);
 
+/* The same product with the rotation on the WEIGHT side, the way the paper's kernel does it (Alg. 2):
+ * every 256-channel block of a weight tile is unpacked, scaled and passed through the inverse
+ * transform on its way into on-chip memory, then multiplied with the un-rotated activations on the
+ * matrix cores; no dequantized weight is written to memory and no workspace is needed.  Results
+ * agree with itq3s_matmul within the same tolerance (the rounding sits on w_hat instead of H x).  It
+ * repeats the transform for every 128-row slab of X and is meant for comparing the two placements,
+ * not as the fast path.  Arguments as for itq3s_matmul; any M with ceil(M/128) <= 65535.
+ * kernel_ms (HOST pointer, may be NULL): if given, the call waits and stores the kernel's duration. */
+int itq3s_matmul_weight_side(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
+                             int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags, void *stream,
+                             float *kernel_ms);
+
 /* Measurement aids: itq3s_matmul / itq3s_matmul_grouped with the same arguments, after which the call
  * WAITS for the work and stores in *kernel_ms (HOST pointer) the duration of the contraction kernel
  * alone (the streaming kernel for M <= 16; for larger M the first tiled launch; not the

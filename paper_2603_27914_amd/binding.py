@@ -25,6 +25,7 @@ EXPORTS = [
     "itq3s_matmul_grouped",
     "itq3s_matmul_grouped_timed",
     "itq3s_matmul_timed",
+    "itq3s_matmul_weight_side",
     "itq3s_read_probe",
     "itq3s_strerror",
     "itq3s_version",
@@ -72,6 +73,8 @@ def lib():
         L.itq3s_matmul_grouped_timed.argtypes = L.itq3s_matmul_grouped.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_matmul_timed.restype = ci
         L.itq3s_matmul_timed.argtypes = L.itq3s_matmul.argtypes + [ctypes.POINTER(ctypes.c_float)]
+        L.itq3s_matmul_weight_side.restype = ci
+        L.itq3s_matmul_weight_side.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp, ctypes.POINTER(ctypes.c_float)]
         L.itq3s_read_probe.restype = ci
         L.itq3s_read_probe.argtypes = [vp, sz, vp, vp]
         L.itq3s_strerror.restype = ctypes.c_char_p
@@ -149,6 +152,27 @@ def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_
         )
     )
     return out
+
+
+def itq3s_matmul_weight_side(codes, scales, N, K, X, out=None, dtype=torch.float32, status_flags=None, timed=False):
+    """Y = X @ W_hat^T with the inverse transform inside the weight tile loader (the paper's placement).
+    timed=True waits and returns (Y, kernel milliseconds)."""
+    _need_cuda(codes, scales, X, out, status_flags)
+    if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
+        raise Itq3sError("X must be float16 [M, K] with unit column stride")
+    M = X.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=X.device)
+    if out.dtype not in (torch.float32, torch.float16) or out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (M, N):
+        raise Itq3sError("out must be float32/float16 [M, N] with unit column stride")
+    ms = ctypes.c_float(0.0)
+    _check(
+        lib().itq3s_matmul_weight_side(
+            _ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
+            out.stride(0), _ptr(status_flags), _stream(), ctypes.byref(ms) if timed else None,
+        )
+    )
+    return (out, float(ms.value)) if timed else out
 
 
 def itq3s_read_probe(buf, sink):

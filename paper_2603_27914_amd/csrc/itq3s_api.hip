@@ -116,6 +116,35 @@ int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64
     return itq3s_matmul_grouped(&w, 1, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream);
 }
 
+int itq3s_matmul_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
+                             void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream, float* kernel_ms) {
+    if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
+    if ((N + 15) / 16 > 0x7fffffffLL / (K / 256) || (M + 127) / 128 > 65535) return ITQ3S_ERR_SHAPE;
+    if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
+    if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) ||
+        (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (kernel_ms) {
+        if (hipEventCreate(&e0) != hipSuccess) return ITQ3S_ERR_LAUNCH;
+        if (hipEventCreate(&e1) != hipSuccess) {
+            (void)hipEventDestroy(e0);
+            return ITQ3S_ERR_LAUNCH;
+        }
+        itq3s::set_launch_timing(e0, e1);
+    }
+    int rc = itq3s::launch_gemm_weight_side(codes, scales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
+    if (kernel_ms) {
+        (void)itq3s::take_launch_timing();
+        if (rc == ITQ3S_OK && (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(kernel_ms, e0, e1) != hipSuccess)) rc = ITQ3S_ERR_LAUNCH;
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+    }
+    return rc;
+}
+
 int itq3s_matmul_grouped_timed(const itq3s_weight* w, int count, int64_t K, const void* X, int64_t M, int64_t ldx, int y_dtype,
                                void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream, float* kernel_ms) {
     if (!kernel_ms) return ITQ3S_ERR_NULL;

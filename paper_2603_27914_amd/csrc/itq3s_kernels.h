@@ -60,4 +60,9 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const _Float16* X, int64_t ldx,
                 int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
 
+// Tiled matmul with the inverse transform applied to the weights inside the tile loader (Alg. 2 as
+// printed); X = the activations themselves.  Any M.
+int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, int64_t M,
+                            void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+
 }  // namespace itq3s

@@ -448,6 +448,42 @@ def test_matmul_grouped_flags_and_determinism(gpu, ref):
             assert torch.equal(u, v)
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 48, 512), (17, 1000, 768), (130, 144, 2048), (300, 600, 1024), (512, 384, 4096)])
+def test_matmul_weight_side_matches_oracle(gpu, ref, M, N, K):
+    """The paper's placement of the transform (inside the weight tile loader): same product, same bar;
+    zero-points over the whole range are exact here (they only touch channel 0 of a block)."""
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "ws-side", z_fraction=0.02)
+    rng = np.random.default_rng(13)
+    z = (scales >> np.uint32(16)).astype(np.uint16).view(np.float16).copy()
+    pick = rng.random(scales.size) < 0.01
+    z[pick] = rng.choice(np.array([-2048, -1000, 1023, 2048], dtype=np.float16), size=int(pick.sum()))
+    scales = (scales & np.uint32(0xffff)) | (z.view(np.uint16).astype(np.uint32) << np.uint32(16))
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    X = synth.activations(M, K, "ws-side", M)
+    want = ref.matmul(codes, scales, N, K, X)
+    for dtype in (torch.float32, torch.float16):
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        got = binding.itq3s_matmul_weight_side(cd, sd, N, K, to_dev(torch, X), dtype=dtype, status_flags=flags).cpu().numpy()
+        assert int(flags.item()) == 0
+        assert rel_rows(got, want) <= (MATMUL_TOL if dtype == torch.float32 else 2 * MATMUL_TOL)
+
+
+def test_matmul_weight_side_full_size_sampled(gpu, ref):
+    torch, binding = gpu
+    N, K, M = 14336, 4096, 512
+    W = synth.weights(N, K, "prefill-ws")
+    codes, scales = binding.itq3s_quantize(to_dev(torch, W))
+    hc, hs = u32(codes), u32(scales)
+    X = synth.activations(M, K, "prefill-ws")
+    got, ms = binding.itq3s_matmul_weight_side(codes, scales, N, K, to_dev(torch, X), timed=True)
+    assert ms > 0.0
+    got = got.cpu().numpy()
+    for n0, n1 in [(0, 40), (7000, 7040), (N - 40, N)]:
+        want = ref.matmul(hc, hs, N, K, X, rows=(n0, n1))
+        assert rel_rows(got[:, n0:n1], want[:, n0:n1]) <= MATMUL_TOL
+
+
 def test_matmul_flags_high_plane(gpu, ref):
     torch, binding = gpu
     codes, scales = synth.random_packed(64, 512, "hp")
