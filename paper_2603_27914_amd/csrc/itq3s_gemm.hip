@@ -216,8 +216,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 // traffic and the weight path needs no barrier.
 //
 // Tile order: workgroups are dealt to the 8 chiplets round-robin by the hardware, so chiplet x takes
-// the contiguous run [x * per, (x+1) * per) of the tile list (m fastest): the workgroups that run
-// together on one chiplet share their weight columns and the activation slab in that chiplet's L2.
+// the contiguous run [x * per, (x+1) * per) of the tile list.  The list walks panels of two tile rows
+// (512 activation rows), inside a panel column by column: the 32 workgroups that run together on one
+// chiplet then cover 2 x 16 tiles and share, in that chiplet's L2, two activation slabs (the expensive
+// operand: 2 bytes per element) among sixteen workgroups each and sixteen weight slabs (0.39 bytes per
+// element) between two.
 constexpr int GM = 256, GN = 256, GK = 64;
 constexpr int GLD = GK + 8;  // LDS row stride in halves: 144 bytes, conflict-free for 16-byte reads
 constexpr int GT = 512;      // threads
@@ -229,7 +232,10 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int t = xcd * per_chiplet + slot;
     if (slot >= per_chiplet || t >= tiles_m * tiles_n) return;
-    const int tn = t / tiles_m, tm = t - tn * tiles_m;
+    constexpr int kPanel = 2;
+    const int panel = t / (kPanel * tiles_n), within = t - panel * (kPanel * tiles_n);
+    const int rows = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;  // the last panel may be short
+    const int tn = within / rows, tm = panel * kPanel + (within - tn * rows);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
@@ -292,10 +298,11 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
             sc[j] = wg_scales[soff[j] + b * kTileRows];
         }
     };
-    // Unpack: a code OR-ed into the mantissa of 1024.0 (bit pattern 0x6400, unit in the last place 1)
-    // is the half 1024 + c; adding -1025 gives the digit c - 1 exactly, times d (exact).
+    // Unpack without shifts: the two code bits of pair p sit at bits 2p+1:2p of each half of the
+    // word.  OR-ed into the mantissa of the half 2^(10-2p) (bit 2p of whose mantissa weighs exactly 1)
+    // they form 2^(10-2p) + c; adding -(2^(10-2p) + 1) gives the digit c - 1 exactly, times d (exact).
+    // One and-or, one add, one multiply per pair of weights.
     half2v dd[2];  // per row: d of the block being unpacked
-    const half2v off = {(_Float16)(-1025.0f), (_Float16)(-1025.0f)};
     uint32_t any_z = 0;  // did one of this lane's rows see a zero-point?
     auto set_scale = [&](const uint32_t (&sc)[2]) {
 #pragma unroll
@@ -311,8 +318,13 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
         uint32_t o[4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            half2v h = __builtin_bit_cast(half2v, ((v >> (2 * p)) & 0x00030003u) | 0x64006400u);
-            h = (h + off) * dd[j];
+            constexpr uint32_t kMagic[4] = {0x64006400u, 0x5C005C00u, 0x54005400u, 0x4C004C00u};  // 1024, 256, 64, 16
+            constexpr float kBase[4] = {1024.0f, 256.0f, 64.0f, 16.0f};
+            uint32_t bits;
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(bits) : "v"(v), "s"(0x00030003u << (2 * p)), "v"(kMagic[p]));
+            const _Float16 o1 = (_Float16)(-(kBase[p] + 1.0f));
+            half2v h = __builtin_bit_cast(half2v, bits);
+            h = (h + half2v{o1, o1}) * dd[j];
             o[p] = __builtin_bit_cast(uint32_t, h);
         }
         const uint4 u = make_uint4(o[0], o[1], o[2], o[3]);
@@ -331,7 +343,7 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
     // and bf (weights), while the activation fragments of the next step are read into an and the
     // weights of the NEXT step (words nw0, nw1 of rows 0, 1) are unpacked into bf for the step after
     // -- the unpack belongs to no LDS stage, so that pipeline runs straight through the barriers.
-    // The scheduling groups ask for the order: the LDS reads, then one matrix instruction and five
+    // The scheduling groups ask for the order: the LDS reads, then one matrix instruction and four
     // vector instructions, eight times.
     half8 bf[2];
     const _Float16* const a_lane = As + (wm * 128 + l32) * GLD + kg * 8;  // + stage*GM*GLD + i*32*GLD + ks*16
@@ -353,7 +365,7 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
     };
 
