@@ -225,6 +225,115 @@ int itq3s_ref_quantize(const float *W, int64_t N, int64_t K, int64_t ldw, uint32
     return 0;
 }
 
+/* ------------------------------------------------------------------ block-size ablation (Sec. 6, "Ablation: FWHT Block Size") */
+
+/* The paper repeats the method with transform lengths n = 32 .. 512 (its table reports perplexity
+ * and kernel overhead per n).  What can be computed without a model is the round trip itself:
+ * per block of n consecutive channels  w' = H_n w,  d = T* sigma(w') -> fp16,  z,  codes (Alg. 1,
+ * Def. 1 exactly as for n = 256), then  w_hat = H_n( d (q - z) )  (Alg. 2, Prop. 1).
+ * H_n is the normalised Hadamard matrix H_u / sqrt(n); 1/sqrt(n) is irrational for n = 32, 128, 512,
+ * so the factor is a fixed fp64 constant (the correctly rounded value) applied with one
+ * multiplication, after the butterflies: w' = (H_u w) * c_n and w_hat = (d * (H_u (q - z))) * c_n.
+ * For n = 256 every step coincides with the functions above. */
+static double ref_inv_sqrt_n(int n)
+{
+    switch (n) {
+    case 32: return 0.17677669529663687;
+    case 64: return 0.125;
+    case 128: return 0.08838834764831843;
+    case 256: return 0.0625;
+    case 512: return 0.044194173824159216;
+    }
+    return 0.0;
+}
+
+static void ref_fwht_n(double *a, int n)
+{
+    for (int step = 1; step < n; step <<= 1)
+        for (int i = 0; i < n; i++)
+            if ((i & step) == 0) {
+                double u = a[i], v = a[i + step];
+                a[i] = u + v;
+                a[i + step] = u - v;
+            }
+}
+
+static double ref_pairwise_sum_n(const double *v, int n)
+{
+    double t[512];
+    memcpy(t, v, (size_t)n * sizeof(double));
+    for (int step = 1; step < n; step <<= 1)
+        for (int i = 0; i < n; i += 2 * step) t[i] = t[i] + t[i + step];
+    return t[0];
+}
+
+/* W: N x K fp32 (row stride ldw), K a multiple of n, n in {32, 64, 128, 256, 512}.
+ * codes_out (N*K bytes, may be NULL): code c = q+1 of every weight, row-major.
+ * scales_out (N*(K/n) words, may be NULL): fp16 d | fp16 z << 16 per block, row-major.
+ * what_out (N*K doubles, may be NULL): reconstructed weights, row-major.
+ * Degenerate and non-finite blocks are handled as in the 256-point quantizer. */
+int itq3s_ref_roundtrip_n(const float *W, int64_t N, int64_t K, int64_t ldw, int n, uint8_t *codes_out, uint32_t *scales_out,
+                          double *what_out, uint32_t *flags)
+{
+    double cn = ref_inv_sqrt_n(n);
+    if (!W) return -1;
+    if (cn == 0.0 || N <= 0 || K <= 0 || (K % n) != 0 || ldw < K) return -2;
+    int64_t KBn = K / n;
+    double a[512], e2[512], m[512];
+    uint8_t c[512];
+    for (int64_t r = 0; r < N; r++)
+        for (int64_t b = 0; b < KBn; b++) {
+            const float *w = W + r * ldw + b * n;
+            int finite = 1;
+            uint32_t word = 0;
+            for (int j = 0; j < n; j++) {
+                a[j] = (double)w[j];
+                if (!isfinite(a[j])) finite = 0;
+                c[j] = 1;
+            }
+            double d = 0.0, z = 0.0;
+            if (!finite) {
+                if (flags) *flags |= REF_FLAG_NONFINITE;
+            } else {
+                ref_fwht_n(a, n);
+                for (int j = 0; j < n; j++) a[j] = a[j] * cn;
+                double mu = ref_pairwise_sum_n(a, n) / (double)n;
+                for (int j = 0; j < n; j++) {
+                    double dev = a[j] - mu;
+                    e2[j] = dev * dev;
+                }
+                double sigma = sqrt(ref_pairwise_sum_n(e2, n) / (double)n);
+                double d64 = ITQ3S_REF_T_STAR * sigma;
+                if (d64 > 65504.0) {
+                    d64 = 65504.0;
+                    if (flags) *flags |= REF_FLAG_SCALE_SAT;
+                }
+                uint16_t dbits = ref_f32_to_f16((float)d64);
+                d = ref_f16_to_f64(dbits);
+                if (d > 0.0) {
+                    double rr = floor(mu / d + 0.5);
+                    z = 0.0 - rr;
+                    if (z > 2048.0) { z = 2048.0; if (flags) *flags |= REF_FLAG_Z_CLAMP; }
+                    if (z < -2048.0) { z = -2048.0; if (flags) *flags |= REF_FLAG_Z_CLAMP; }
+                    double t_hi = (0.5 - z) * d, t_lo = (-0.5 - z) * d;
+                    for (int j = 0; j < n; j++) c[j] = (uint8_t)(a[j] >= t_hi ? 2 : (a[j] < t_lo ? 0 : 1));
+                    word = (uint32_t)dbits | ((uint32_t)ref_f32_to_f16((float)z) << 16);
+                } else {
+                    d = 0.0;
+                }
+            }
+            if (codes_out) memcpy(codes_out + r * K + b * n, c, (size_t)n);
+            if (scales_out) scales_out[r * KBn + b] = word;
+            if (what_out) {
+                for (int j = 0; j < n; j++) m[j] = (double)((int)c[j] - 1) - z;
+                if (!(d > 0.0)) for (int j = 0; j < n; j++) m[j] = 0.0;
+                ref_fwht_n(m, n);
+                for (int j = 0; j < n; j++) what_out[r * K + b * n + j] = (d * m[j]) * cn;
+            }
+        }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ dequantize (Alg. 2, Prop. 1) */
 
 /* w_hat = H ( d_k (q - z_k) ): unpack, subtract the code zero-point 1 and z_k, run the same

@@ -42,6 +42,7 @@ def lib():
         L.itq3s_ref_dequantize.argtypes = [u32p, u32p, i64, i64, vp, i64, u32p]
         L.itq3s_ref_matmul.argtypes = [u32p, u32p, i64, i64, vp, i64, i64, vp, i64]
         L.itq3s_ref_matmul_rows.argtypes = [u32p, u32p, i64, i64, vp, i64, i64, vp, i64, i64, i64]
+        L.itq3s_ref_roundtrip_n.argtypes = [vp, i64, i64, i64, ctypes.c_int, vp, u32p, vp, u32p]
         L.itq3s_ref_fwht256.argtypes = [vp]
         L.itq3s_ref_fwht256.restype = None
         L.itq3s_ref_forward_block.argtypes = [vp, vp]
@@ -110,6 +111,20 @@ def quantize(W):
     flags = np.zeros(1, dtype=np.uint32)
     _check(lib().itq3s_ref_quantize(_ptr(W), N, K, W.strides[0] // 4, _ptr(codes), _ptr(scales), _ptr(flags)))
     return codes, scales, int(flags[0])
+
+
+def roundtrip_n(W, n):
+    """Block-size ablation: quantize and reconstruct W fp32 [N, K] with blocks of n channels.
+    -> (codes uint8 [N, K], scale words uint32 [N, K/n], W_hat fp64 [N, K], flags)."""
+    W = np.asarray(W)
+    assert W.dtype == np.float32 and W.ndim == 2 and W.strides[1] == 4
+    N, K = W.shape
+    codes = np.zeros((N, K), dtype=np.uint8)
+    scales = np.zeros((N, K // n), dtype=np.uint32)
+    what = np.zeros((N, K), dtype=np.float64)
+    flags = np.zeros(1, dtype=np.uint32)
+    _check(lib().itq3s_ref_roundtrip_n(_ptr(W), N, K, W.strides[0] // 4, n, _ptr(codes), _ptr(scales), _ptr(what), _ptr(flags)))
+    return codes, scales, what, int(flags[0])
 
 
 def dequantize(codes, scales, N, K, return_flags=False):
