@@ -30,6 +30,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+FP64_VECTOR_PEAK_TFLOPS = 78.6
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 
@@ -88,7 +89,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
     ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
-    ap.add_argument("--legs", default="per_shape,read_floor,stream70b,prefill,dequantize,copy,cpu", help="comma list of the extra legs to run")
+    ap.add_argument("--legs", default="per_shape,read_floor,stream70b,prefill,dequantize,ablation,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -239,6 +240,8 @@ def main():
         out["prefill"] = prefill_leg(torch, binding, synth, gen)
     if "dequantize" in legs:
         out["dequantize"] = dequantize_leg(torch, binding, tensors)
+    if "ablation" in legs:
+        out["block_size_ablation"] = ablation_leg(torch, binding, gen)
     if "stream70b" in legs and args.workload != "llama70b_decode":
         out["stream70b"] = stream70b_leg(torch, binding, synth, gen)
     if "read_floor" in legs:
@@ -351,6 +354,35 @@ def dequantize_leg(torch, binding, tensors):
     nbytes = packed_bytes(N, K) + N * K * 4
     return {"N": N, "K": K, "us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "output_buffers": nout}
+
+
+def ablation_leg(torch, binding, gen, N=8192, K=8192, copies=3):
+    """Block-size ablation (Sec. 6): the rotate - quantize - reconstruct round trip with transform
+    lengths 32 .. 512 over the same heavy-tailed fp32 weights; the error sums are reduced on the
+    device (no output tensors), so a launch reads 4 bytes per weight.  The copies (768 MB together)
+    are cycled so that the reads come from HBM."""
+    Ws = [student_t_weights(torch, gen, N, K) for _ in range(copies)]
+    res = []
+    for n in (32, 64, 128, 256, 512):
+        err2 = torch.zeros(2, dtype=torch.float64, device="cuda")
+        binding.itq3s_roundtrip(Ws[0], n, codes=False, scales=False, w_hat=False, err2=err2)
+        e = err2.cpu().numpy()
+        state = {"i": 0}
+
+        def run():
+            state["i"] += 1
+            binding.itq3s_roundtrip(Ws[state["i"] % copies], n, codes=False, scales=False, w_hat=False, err2=err2)
+
+        ms = time_calls(torch, run, 4 * copies, warm=copies)
+        nbytes = N * K * 4
+        # fp64 operations per weight: two transforms of log2(n) additions each, about 20 more for the
+        # scaling, statistics, thresholds, reconstruction and error sums; none of them fused, so the
+        # ceiling is half the chip's fp64 vector rate (which counts a fused multiply-add as two)
+        ops = (2 * (n.bit_length() - 1) + 20) * N * K
+        res.append({"block_size": n, "bits_per_weight": round(3.0 + 32.0 / n, 4), "rel_rmse": round(float((e[0] / e[1]) ** 0.5), 5),
+                    "us": round(ms * 1e3, 1), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                    "fp64_Tops": round(ops / (ms * 1e-3) / 1e12, 2), "frac_of_unfused_fp64_peak": round(ops / (ms * 1e-3) / 1e12 / (FP64_VECTOR_PEAK_TFLOPS / 2), 4)})
+    return {"N": N, "K": K, "dtype": "f64", "bound": "alu", "sizes": res}
 
 
 def stream70b_leg(torch, binding, synth, gen, n_layers=80):

@@ -132,6 +132,27 @@ int itq3s_matmul_weight_side(const uint32_t *codes, const uint32_t *scales, int6
                              int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags, void *stream,
                              float *kernel_ms);
 
+/* Block-size ablation (Sec. 6, "Ablation: FWHT Block Size"): rotate, quantize and reconstruct with a
+ * transform length block_size in {32, 64, 128, 256, 512} instead of the format's 256, without
+ * packing.  Per block of block_size consecutive channels of a row the steps are those of
+ * itq3s_quantize (fp64, fixed order, 1/sqrt(block_size) applied once after the butterflies, scale
+ * rounded to fp16, zero-point, exact thresholds) followed by w_hat = H(d (q - z)) (Alg. 2, Prop. 1),
+ * rounded once to fp32.  With block_size 256 the codes and scale words equal what itq3s_quantize
+ * packs and w_hat agrees with itq3s_dequantize's fp32 output.
+ *   W (device, const): N x K fp32, row stride ldw >= K, ldw % 4 == 0, 16-byte aligned
+ *   K % block_size == 0
+ *   codes_out (device, may be NULL): N x K bytes, one code 0/1/2 per channel, 16-byte aligned
+ *   scales_out (device, may be NULL): N x (K / block_size) words, d | z << 16 as in the packed format
+ *   W_hat (device, may be NULL): N x K fp32, row stride ldo >= K, ldo % 4 == 0, 16-byte aligned
+ *   err2 (device, may be NULL): two doubles the call ADDS to (zero them first): [0] += sum (w_hat - w)^2,
+ *       [1] += sum w^2 over all blocks without non-finite weights.  The additions are atomic and
+ *       their order is not fixed: the sums are reproducible to rounding only.
+ *   status_flags: as for itq3s_quantize
+ * Blocks with a non-finite weight or a zero scale give codes 1, scale word 0, w_hat 0.
+ * Returns ITQ3S_ERR_SHAPE for any other block_size. */
+int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block_size, uint8_t *codes_out, uint32_t *scales_out,
+                    float *W_hat, int64_t ldo, double *err2, uint32_t *status_flags, void *stream);
+
 /* Measurement aids: itq3s_matmul / itq3s_matmul_grouped with the same arguments, after which the call
  * WAITS for the work and stores in *kernel_ms (HOST pointer) the duration of the contraction kernel
  * alone (the streaming kernel for M <= 16; for larger M the first tiled launch; not the

@@ -21,6 +21,7 @@ EXPORTS = [
     "itq3s_matmul_workspace_bytes",
     "itq3s_quantize",
     "itq3s_dequantize",
+    "itq3s_roundtrip",
     "itq3s_matmul",
     "itq3s_matmul_grouped",
     "itq3s_matmul_grouped_timed",
@@ -65,6 +66,8 @@ def lib():
         L.itq3s_quantize.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
         L.itq3s_dequantize.restype = ci
         L.itq3s_dequantize.argtypes = [vp, vp, i64, i64, vp, ci, i64, vp, vp]
+        L.itq3s_roundtrip.restype = ci
+        L.itq3s_roundtrip.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, i64, vp, vp, vp]
         L.itq3s_matmul.restype = ci
         L.itq3s_matmul.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
         L.itq3s_matmul_grouped.restype = ci
@@ -152,6 +155,46 @@ def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_
         )
     )
     return out
+
+
+def itq3s_roundtrip(W, block_size, codes=True, scales=True, w_hat=True, err2=None, status_flags=None):
+    """Rotate - quantize - reconstruct with transform length block_size (32 .. 512), unpacked.
+
+    W: float32 [N, K] device tensor.  codes / scales / w_hat: True to allocate, False to skip, or a
+    tensor to fill (uint8 [N, K], int32 [N, K/block_size], float32 [N, K]).  err2: float64[2] device
+    tensor the call adds (sum of squared errors, sum of squared weights) to, or None.
+    -> (codes, scales, w_hat), None where skipped."""
+    _need_cuda(W, err2, status_flags)
+    if W.dtype != torch.float32 or W.dim() != 2 or W.stride(1) != 1:
+        raise Itq3sError("W must be float32 [N, K] with unit column stride")
+    N, K = W.shape
+    if block_size <= 0 or K % block_size != 0:
+        raise Itq3sError("K must be a multiple of block_size")
+
+    def want(arg, shape, dtype):
+        if arg is True:
+            return torch.empty(shape, dtype=dtype, device=W.device)
+        if arg is False or arg is None:
+            return None
+        _need_cuda(arg)
+        if arg.dtype != dtype or tuple(arg.shape) != shape or arg.stride(-1) != 1:
+            raise Itq3sError("output tensor must be %s %s with unit column stride" % (dtype, shape))
+        return arg
+
+    codes = want(codes, (N, K), torch.uint8)
+    scales = want(scales, (N, K // block_size), torch.int32)
+    w_hat = want(w_hat, (N, K), torch.float32)
+    if (codes is not None and not codes.is_contiguous()) or (scales is not None and not scales.is_contiguous()):
+        raise Itq3sError("codes and scales must be contiguous")
+    if err2 is not None and (err2.dtype != torch.float64 or err2.numel() != 2 or not err2.is_contiguous()):
+        raise Itq3sError("err2 must be a contiguous float64[2] tensor")
+    _check(
+        lib().itq3s_roundtrip(
+            _ptr(W), N, K, W.stride(0), block_size, _ptr(codes), _ptr(scales), _ptr(w_hat), w_hat.stride(0) if w_hat is not None else 0,
+            _ptr(err2), _ptr(status_flags), _stream()
+        )
+    )
+    return codes, scales, w_hat
 
 
 def itq3s_matmul_weight_side(codes, scales, N, K, X, out=None, dtype=torch.float32, status_flags=None, timed=False):

@@ -58,6 +58,19 @@ int itq3s_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* 
     return itq3s::launch_quantize(W, N, K, ldw, codes, scales, status_flags, static_cast<hipStream_t>(stream));
 }
 
+int itq3s_roundtrip(const float* W, int64_t N, int64_t K, int64_t ldw, int block_size, uint8_t* codes_out, uint32_t* scales_out,
+                    float* W_hat, int64_t ldo, double* err2, uint32_t* status_flags, void* stream) {
+    if (!W) return ITQ3S_ERR_NULL;
+    if (block_size != 32 && block_size != 64 && block_size != 128 && block_size != 256 && block_size != 512) return ITQ3S_ERR_SHAPE;
+    if (N <= 0 || K <= 0 || K % block_size != 0 || ldw < K || (W_hat && ldo < K)) return ITQ3S_ERR_SHAPE;
+    if (N > 0x7fffffffLL / ((K + 1023) / 1024)) return ITQ3S_ERR_SHAPE;  // one wavefront per 1024 channels of a row
+    if (!aligned(W, 16) || ldw % 4 != 0 || (codes_out && !aligned(codes_out, 16)) || (scales_out && !aligned(scales_out, 4)) ||
+        (W_hat && (!aligned(W_hat, 16) || ldo % 4 != 0)) || (err2 && !aligned(err2, 8)) || (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    return itq3s::launch_roundtrip(W, N, K, ldw, block_size, codes_out, scales_out, W_hat, ldo, err2, status_flags,
+                                   static_cast<hipStream_t>(stream));
+}
+
 int itq3s_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* W_out, int out_dtype, int64_t ldo,
                      uint32_t* status_flags, void* stream) {
     if (!codes || !scales || !W_out) return ITQ3S_ERR_NULL;

@@ -65,4 +65,9 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
 int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, int64_t M,
                             void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
 
+// Round trip with transform length n in {32 .. 512} (block-size ablation, Sec. 6); any of codes,
+// scales, What, err may be null.  Returns -2 for another n.
+int launch_roundtrip(const float* W, int64_t N, int64_t K, int64_t ldw, int n, uint8_t* codes, uint32_t* scales, float* What, int64_t ldo,
+                     double* err, uint32_t* flags, hipStream_t stream);
+
 }  // namespace itq3s

@@ -16,26 +16,6 @@ namespace itq3s {
 
 constexpr double kTStar = 0.7979;  // optimal ternary scale / sigma (Sec. 3.3, App. A)
 
-// value of lane (l ^ MASK), MASK in {1, 2, 4, 8}: moves inside a row of 16 lanes
-template <int MASK>
-__device__ __forceinline__ int row_xor_i32(int x) {
-    // (every lane reads a valid lane, so no previous value of the destination is needed)
-    if constexpr (MASK == 1) return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true);       // quad_perm [1,0,3,2]
-    else if constexpr (MASK == 2) return __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
-    else if constexpr (MASK == 4) {  // l^7 (mirror in 8) then l^3 (reverse in 4)
-        x = __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true);
-        return __builtin_amdgcn_mov_dpp(x, 0x1B, 0xf, 0xf, true);
-    } else {  // l^15 (mirror in 16) then l^7
-        x = __builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true);
-        return __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true);
-    }
-}
-template <int MASK>
-__device__ __forceinline__ double row_xor_f64(double v) {
-    const int lo = row_xor_i32<MASK>(__double2loint(v)), hi = row_xor_i32<MASK>(__double2hiint(v));
-    return __hiloint2double(hi, lo);
-}
-
 // One cross-lane butterfly stage: the lower lane of a pair gets u + v, the upper one u - v (u the
 // lower lane's value).  The upper lane forms (-v) + u, which is u - v bit for bit.
 template <int MASK>
