@@ -31,6 +31,7 @@ constexpr int BM = 128, BN = 128, BK = 64;
 // the 256 x 256 variant below takes over when there are enough rows to fill its tiles and enough
 // tiles to occupy the chip
 constexpr int kGemmBigMinM = 192, kGemmBigMinTiles = 128;
+constexpr int64_t kGemmBigMaxK = 1 << 21;  // its per-lane byte offsets (up to 256 rows x K x 2) are 32-bit
 constexpr int LDT = BK + 8;  // LDS row stride in halves (padding keeps 16-byte reads conflict-free)
 
 struct GemmArgs {
@@ -44,30 +45,46 @@ struct GemmArgs {
     int NT, KB, y_f16;
 };
 
-// Zero-point term of one 32 x 32 output block that has already been stored: column n (this lane's),
-// rows row0 + 8*(v/4) + 4*kg + v%4.  Walks the column's scale words and, for blocks with z != 0,
-// subtracts d z 16 x[m][256 b] from the stored outputs (each output belongs to one lane).  Working
-// on memory keeps the rare path out of the register budget of the main loop.
-__device__ __forceinline__ void subtract_zero_points(const GemmArgs& a, int64_t n, int64_t row0, int kg) {
-    if (n >= a.N) return;
-    const uint32_t* sc = a.scales + (n >> 4) * a.KB * kTileRows + (n & 15);
+// Zero-point term of a wavefront's output block that has already been stored: columns
+// n_first .. n_first + 63, rows m_first .. m_first + MROWS - 1.  Lane l walks the scale words of
+// column n_first + l, sixteen blocks per batch (independent loads).  For each block with z != 0 -- a
+// fraction of a percent on real weights -- the whole wavefront subtracts d z 16 x[m][256 b] from that
+// column, one row per lane.  Per output element the blocks are applied in ascending order by one lane
+// at a time, so the result does not depend on scheduling.  Working on memory keeps the rare path
+// out of the register budget of the main loop.
+template <int MROWS>
+__device__ __forceinline__ void subtract_zero_points_wave(const GemmArgs& a, int64_t n_first, int64_t m_first, int lane) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's own stores of the block have completed
+    const int64_t n = n_first + lane;
+    const int64_t nc = n < a.N ? n : a.N - 1;
+    const uint32_t* sc = a.scales + (nc >> 4) * a.KB * kTileRows + (nc & 15);
 #pragma unroll 1
-    for (int b = 0; b < a.KB; ++b) {
-        const uint32_t w = sc[(int64_t)b * kTileRows];
-        const float z = f16_bits_to_f32(w >> 16);
-        if (z != 0.f) {
-            const float dz = f16_bits_to_f32(w & 0xffffu) * z;
+    for (int b0 = 0; b0 < a.KB; b0 += 16) {
+        uint32_t w[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) w[u] = sc[(int64_t)(b0 + u < a.KB ? b0 + u : a.KB - 1) * kTileRows];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const bool hit = (w[u] & 0x7fff0000u) != 0u && n < a.N && b0 + u < a.KB;
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(hit);
+            while (todo != 0ull) {  // uniform
+                const int src = __builtin_ctzll(todo);
+                todo &= todo - 1ull;
+                const uint32_t word = (uint32_t)__builtin_amdgcn_readlane((int)w[u], src);
+                const float dz = f16_bits_to_f32(word & 0xffffu) * f16_bits_to_f32(word >> 16);
+                const int64_t nh = n_first + src;
 #pragma unroll 1
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = row0 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                if (m < a.M) {
-                    const float t = dz * (16.0f * (float)a.X[m * a.ldx + (int64_t)b * kBlock]);
-                    if (a.y_f16) {
-                        _Float16* y = reinterpret_cast<_Float16*>(a.Y) + m * a.ldy + n;
-                        *y = (_Float16)((float)*y - t);
-                    } else {
-                        float* y = reinterpret_cast<float*>(a.Y) + m * a.ldy + n;
-                        *y = *y - t;
+                for (int r = 0; r < MROWS; r += kWave) {
+                    const int64_t m = m_first + r + lane;
+                    if (m < a.M) {
+                        const float t = dz * (16.0f * (float)a.X[m * a.ldx + (int64_t)(b0 + u) * kBlock]);
+                        if (a.y_f16) {
+                            _Float16* y = reinterpret_cast<_Float16*>(a.Y) + m * a.ldy + nh;
+                            *y = (_Float16)((float)*y - t);
+                        } else {
+                            float* y = reinterpret_cast<float*>(a.Y) + m * a.ldy + nh;
+                            *y = *y - t;
+                        }
                     }
                 }
             }
@@ -191,29 +208,44 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
             }
         }
     // zero-point term, only if some block of the workgroup's 128 rows has one
-    if (__syncthreads_or(any_z != 0u)) {
-#pragma unroll 1
-        for (int ij = 0; ij < 4; ++ij) {
-            const int i = ij >> 1, j = ij & 1;
-            subtract_zero_points(a, (int64_t)nt0 * 16 + wn * 64 + j * 32 + l32, m0 + wm * 64 + i * 32, kg);
-        }
-    }
+    if (__syncthreads_or(any_z != 0u)) subtract_zero_points_wave<64>(a, (int64_t)nt0 * 16 + wn * 64, m0 + wm * 64, lane);
     if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Large-M variant: workgroup tile 256 (m) x 256 (n), eight wavefronts as 2 (m) x 4 (n), wavefront
 // tile 128 x 64 = 4 x 2 v_mfma_f32_32x32x16_f16 (128 accumulator registers per lane, two wavefronts
-// per SIMD so that one unpacks while the other multiplies).
+// per SIMD so that one unpacks while the other multiplies), K in quarters of a block (64 channels =
+// four MFMA steps), one barrier per quarter.
 //
-// Only the activations go through LDS (two stages of 256 rows x 64 channels, one barrier per stage).
-// The weights never do: a lane of the 32x32x16 product supplies, for its column n, eight consecutive
-// channels k' of the step -- and one low-plane word of the packed tile holds exactly the 16 channels
-// of one step of one row, in k' order after the shift-and-mask unpack (pairs (slot j, slot j+8)).
-// So every lane loads the words of its own two rows (16 bytes = four steps per load), turns its
-// half of a word into four half2 values d (c - 1) in registers, and feeds the matrix core.  The
-// two wavefronts that share a column range repeat that unpack; in exchange the LDS carries half the
-// traffic and the weight path needs no barrier.
+// A lane of the 32x32x16 product supplies, for its column n, eight consecutive channels k' of the
+// step -- and one low-plane word of the packed tile holds exactly the 16 channels of one step of one
+// row, in k' order after the unpack (pairs (slot j, slot j+8)).  So a lane needs, per quarter, the
+// four words (16 bytes) of each of its two rows, turns its half of a word into four half2 values
+// d (c - 1) in registers, and feeds the matrix core; no dequantized tile is ever stored.  The two
+// wavefronts that share a column range repeat that unpack.
+//
+// Every operand is copied global -> LDS by the memory pipe itself (buffer_load ... lds: no registers,
+// no LDS store instructions), two to three quarters ahead of the arithmetic -- about 1.5 us of lead,
+// which covers an HBM miss.
+//
+// LDS (136 KiB):
+//   activations  ring of 3 quarters x 256 rows x 128 bytes, no padding (one copy instruction writes
+//                1 KiB = 8 rows, lane l the 16-byte piece l of it).  To keep the 16-byte fragment
+//                reads conflict-free, piece p of row r holds channel chunk p ^ swz(r),
+//                swz(r) = (r & 7) ^ ((r >> 3) & 1): sixteen consecutive rows reading the same chunk
+//                touch sixteen different 16-byte groups of 256 bytes, eight rows eight groups of 128.
+//   weights      ring of 4 quarters x 8 wavefronts x 1 KiB: lane (l32, kg) copies the 16 bytes of ITS
+//                row j = kg, and later reads both rows (its own piece and that of lane (l32, 1 - kg)).
+//                Private to the wavefront: ordered by the load counter alone, no barrier.
+//   scales       ring of 4 quarters x 8 wavefronts x 256 bytes, same pattern with 4 bytes per lane.
+// The weight ring runs one quarter further ahead than the activation ring because the last MFMA step
+// of a quarter already unpacks the first words of the next one.
+//
+// All LDS reads are written as inline instructions with their own counter waits: the compiler orders
+// every LDS read it can see after ALL outstanding global -> LDS copies, which would drain the
+// look-ahead at the first read of each quarter.  Since no load returns into registers, it inserts no
+// load-counter waits of its own inside the loop either; the explicit ones are all there are.
 //
 // Tile order: workgroups are dealt to the 8 chiplets round-robin by the hardware, so chiplet x takes
 // the contiguous run [x * per, (x+1) * per) of the tile list.  The list walks panels of two tile rows
@@ -222,97 +254,128 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 // operand: 2 bytes per element) among sixteen workgroups each and sixteen weight slabs (0.39 bytes per
 // element) between two.
 constexpr int GM = 256, GN = 256, GK = 64;
-constexpr int GLD = GK + 8;  // LDS row stride in halves: 144 bytes, conflict-free for 16-byte reads
-constexpr int GT = 512;      // threads
-constexpr int kGemmBigLds = 2 * GM * GLD * 2;  // bytes, dynamic (above the 64 KB static limit)
+constexpr int GT = 512;  // threads
+constexpr int kXStages = 3, kWStages = 4;
+constexpr int kXStageBytes = GM * GK * 2;                   // 32768
+constexpr int kWRingBase = kXStages * kXStageBytes;         // 98304
+constexpr int kWStageBytes = 8 * 1024;                      // 8 wavefronts x 64 lanes x 16 bytes
+constexpr int kSRingBase = kWRingBase + kWStages * kWStageBytes;  // 131072
+constexpr int kSStageBytes = 8 * 256;                       // 8 wavefronts x 64 lanes x 4 bytes
+constexpr int kGemmDmaLds = kSRingBase + kWStages * kSStageBytes;  // 139264
+
+template <int OFF>
+__device__ __forceinline__ half8 lds_read_b128(uint32_t addr) {
+    half8 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+    return r;
+}
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_u4(uint32_t addr) {
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+    return r;
+}
+template <int OFF>
+__device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr) {
+    uint32_t r;
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF) : "memory");
+    return r;
+}
+// wait until at most N LDS reads are outstanding; the values are passed through so that no use of
+// them can be scheduled ahead of the wait
+#define ITQ3S_LDS_WAIT(N, af) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(af[0]), "+v"(af[1]), "+v"(af[2]), "+v"(af[3]))
 
 __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
-    extern __shared__ __align__(16) _Float16 As[];  // [2][GM * GLD]
+    extern __shared__ __align__(1024) char lds[];
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int t = xcd * per_chiplet + slot;
     if (slot >= per_chiplet || t >= tiles_m * tiles_n) return;
     constexpr int kPanel = 2;
     const int panel = t / (kPanel * tiles_n), within = t - panel * (kPanel * tiles_n);
-    const int rows = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;  // the last panel may be short
+    const int rows = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;
     const int tn = within / rows, tm = panel * kPanel + (within - tn * rows);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 2, wn = wave & 3;
     const int l32 = lane & 31, kg = lane >> 5;
     const int64_t m0 = (int64_t)tm * GM;
     const int64_t n0 = (int64_t)tn * GN;
-
-    // Every load below is unconditional (rows past M or N and steps past K are clamped to valid
-    // memory; what they produce lands in outputs that are never stored), so the loop is straight-line
-    // and the load counter alone orders loads and use.
-    // ---- activation loader: four 16-byte pieces per thread and stage (row = idx/8, piece = idx%8),
-    // loaded one stage (four MFMA steps) before they are written to LDS
-    u32x4 xa0, xa1, xa2, xa3;  // (plain variables: an array shared by two lambdas stays in memory)
-    const int xr = tid >> 3, xc = tid & 7;  // rows xr, xr+64, xr+128, xr+192
-    const _Float16* xrow[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) xrow[i] = a.Xt + (m0 + xr + 64 * i < a.M ? m0 + xr + 64 * i : a.M - 1) * a.K + xc * 8;
     const int KT = (int)(a.K / GK);
-    auto load_x = [&](int kt) {
-        const int k = (kt < KT ? kt : KT - 1) * GK;
-        xa0 = *reinterpret_cast<const u32x4*>(xrow[0] + k);
-        xa1 = *reinterpret_cast<const u32x4*>(xrow[1] + k);
-        xa2 = *reinterpret_cast<const u32x4*>(xrow[2] + k);
-        xa3 = *reinterpret_cast<const u32x4*>(xrow[3] + k);
+
+    // All copies go through buffer descriptors: a 32-bit per-lane offset fixed for the whole kernel
+    // plus a scalar offset that advances with the stage -- no address arithmetic in the vector pipe.
+    // Steps past the end of K repeat the last stage (valid memory, never consumed).
+    constexpr int kRsrcFlags = 0x00027000;  // raw buffer, 32-bit elements
+    // ---- activations: wavefront w copies pieces 4w .. 4w+3 of a stage (8 rows each); lane l supplies
+    // row l/8 of the piece and the chunk that belongs at position l%8 of that row.  Rows past M read
+    // row M-1 (their outputs are never stored).
+    const __amdgpu_buffer_rsrc_t x_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(a.Xt + m0 * a.K), 0, (int)(GM * a.K * 2), kRsrcFlags);
+    int xoff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int64_t row = 8 * (4 * wave + i) + (lane >> 3);
+        if (m0 + row > a.M - 1) row = a.M - 1 - m0;
+        const int chunk = (lane & 7) ^ (lane >> 3) ^ (i & 1);
+        xoff[i] = (int)(row * a.K * 2 + chunk * 16);
+    }
+    // ---- weights: the lane's OWN row n = n0 + wn*64 + kg*32 + l32, as byte offsets from the
+    // workgroup's first tile row (16 tile rows x KB tiles: far below 2^31 bytes for any K accepted here)
+    const int64_t nt0 = n0 >> 4;
+    const int64_t wg_tile_rows = a.NT - nt0 < 16 ? a.NT - nt0 : 16;
+    const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t*>(a.codes + nt0 * a.KB * kTileWords), 0, (int)(wg_tile_rows * a.KB * kTileWords * 4), kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint32_t*>(a.scales + nt0 * a.KB * kTileRows), 0, (int)(wg_tile_rows * a.KB * kTileRows * 4), kRsrcFlags);
+    int woff, soff;
+    {
+        const int r16 = l32 & 15;
+        int64_t tr = wn * 4 + (l32 >> 4) + 2 * kg;
+        if (nt0 + tr > a.NT - 1) tr = a.NT - 1 - nt0;
+        woff = (int)(tr * a.KB * kTileWords + 4 * r16) * 4;  // low-plane words of storage lane 16 q + r16: + 256 q bytes
+        soff = (int)(tr * a.KB * kTileRows + r16) * 4;
+    }
+    auto copy_x = [&](int kt, int ring) {
+        const int k_bytes = (kt < KT ? kt : KT - 1) * (GK * 2);
+        char* dst = lds + ring * kXStageBytes + 4096 * wave;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (__attribute__((address_space(3))) void*)(dst + 1024 * i), 16, xoff[i], k_bytes, 0, 0);
     };
-    auto store_x = [&](int stage) {
-        _Float16* dst = As + stage * (GM * GLD) + xr * GLD + xc * 8;
-        *reinterpret_cast<u32x4*>(dst) = xa0;
-        *reinterpret_cast<u32x4*>(dst + 64 * GLD) = xa1;
-        *reinterpret_cast<u32x4*>(dst + 128 * GLD) = xa2;
-        *reinterpret_cast<u32x4*>(dst + 192 * GLD) = xa3;
+    auto copy_w = [&](int kt_) {  // quarter kt of the rows: block kt/4, quarter kt%4; ring position kt%4
+        const int kt = kt_ < KT ? kt_ : KT - 1;
+        const int b = kt >> 2, q = kt & 3, ring = kt_ & 3;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(c_rsrc, (__attribute__((address_space(3))) void*)(lds + kWRingBase + ring * kWStageBytes + 1024 * wave),
+                                                 16, woff, b * (kTileWords * 4) + 256 * q, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(s_rsrc, (__attribute__((address_space(3))) void*)(lds + kSRingBase + ring * kSStageBytes + 256 * wave),
+                                                 4, soff, b * (kTileRows * 4), 0, 0);
     };
 
-    // ---- weight loader: this lane's two rows n = n0 + wn*64 + j*32 + l32.  Row j sits 2j tile rows
-    // below row 0; offsets are 32-bit, relative to the workgroup's first tile row (its 16 tile rows
-    // span 16*KB tiles, far below 2^31 words for any K this library accepts).
-    const int64_t nt0 = n0 >> 4;
-    const uint32_t* const wg_codes = a.codes + nt0 * a.KB * kTileWords;
-    const uint32_t* const wg_scales = a.scales + nt0 * a.KB * kTileRows;
-    const int r16 = l32 & 15;
-    uint32_t woff[2], soff[2];
+    // ---- fragment reads: row wm*128 + i*32 + l32, chunk 2 ks + kg, at position chunk ^ swz(row);
+    // swz depends on l32 only, so one byte offset per step ks serves all four i (+ 4096 i)
+    uint32_t aoff[4];
+    {
+        const int s = (l32 & 7) ^ ((l32 >> 3) & 1);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        int64_t tr = wn * 4 + (l32 >> 4) + 2 * j;
-        if (nt0 + tr > a.NT - 1) tr = a.NT - 1 - nt0;
-        woff[j] = (uint32_t)tr * (uint32_t)a.KB * kTileWords + 4 * r16;
-        soff[j] = (uint32_t)tr * (uint32_t)a.KB * kTileRows + r16;
+        for (int ks = 0; ks < 4; ++ks) aoff[ks] = (uint32_t)((wm * 128 + l32) * 128 + (((2 * ks + kg) ^ s) * 16));
     }
-    uint32_t bad = 0;
-    const int QT = KT;  // quarters of a block: 64 channels = one LDS stage = four MFMA steps
-    uint2 hi0, hi1;  // high-plane words of the quarter in flight; folded into `bad` a stage later
-    auto load_w = [&](int qt_, uint4 (&w)[2], uint32_t (&sc)[2]) {  // quarter of the row: block qt/4, quarter qt%4
-        const int qt = qt_ < QT ? qt_ : QT - 1;
-        const uint32_t b = (uint32_t)qt >> 2, q = (uint32_t)qt & 3;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t* tile = wg_codes + (woff[j] + b * kTileWords);  // low-plane words of lane 16q + r16 start at + 64q
-            w[j] = *reinterpret_cast<const uint4*>(tile + 64 * q);
-            (j == 0 ? hi0 : hi1) = *reinterpret_cast<const uint2*>(tile + kTileLoWords + 32 * q - 2 * r16);
-            sc[j] = wg_scales[soff[j] + b * kTileRows];
-        }
+    const uint32_t wread = (uint32_t)(kWRingBase + 1024 * wave + 16 * l32);  // row 0 here, row 1 at + 512
+    const uint32_t sread = (uint32_t)(kSRingBase + 256 * wave + 4 * l32);    // row 0 here, row 1 at + 128
+
+    uint32_t any_z = 0;
+    half2v dd[2];
+    auto set_scale = [&](uint32_t s0, uint32_t s1) {
+        const _Float16 d0 = __builtin_bit_cast(_Float16, (uint16_t)(s0 & 0xffffu)), d1 = __builtin_bit_cast(_Float16, (uint16_t)(s1 & 0xffffu));
+        dd[0] = half2v{d0, d0};
+        dd[1] = half2v{d1, d1};
+        any_z |= ((s0 | s1) >> 16) & 0x7fffu;
     };
     // Unpack without shifts: the two code bits of pair p sit at bits 2p+1:2p of each half of the
     // word.  OR-ed into the mantissa of the half 2^(10-2p) (bit 2p of whose mantissa weighs exactly 1)
     // they form 2^(10-2p) + c; adding -(2^(10-2p) + 1) gives the digit c - 1 exactly, times d (exact).
     // One and-or, one add, one multiply per pair of weights.
-    half2v dd[2];  // per row: d of the block being unpacked
-    uint32_t any_z = 0;  // did one of this lane's rows see a zero-point?
-    auto set_scale = [&](const uint32_t (&sc)[2]) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(sc[j] & 0xffffu));
-            dd[j] = half2v{d, d};
-            any_z |= (sc[j] >> 16) & 0x7fffu;
-        }
-    };
-    // word = the 16 channels of one MFMA step of row j; this lane's eight are the pairs 4kg .. 4kg+3
     auto unpack = [&](uint32_t word, int j) -> half8 {
         const uint32_t v = word >> (8 * kg);
         uint32_t o[4];
@@ -339,18 +402,7 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // One MFMA step: 4 x 2 products on the fragments af (activations, read from LDS a step earlier)
-    // and bf (weights), while the activation fragments of the next step are read into an and the
-    // weights of the NEXT step (words nw0, nw1 of rows 0, 1) are unpacked into bf for the step after
-    // -- the unpack belongs to no LDS stage, so that pipeline runs straight through the barriers.
-    // The scheduling groups ask for the order: the LDS reads, then one matrix instruction and four
-    // vector instructions, eight times.
     half8 bf[2];
-    const _Float16* const a_lane = As + (wm * 128 + l32) * GLD + kg * 8;  // + stage*GM*GLD + i*32*GLD + ks*16
-    auto read_a = [&](int stage, int ks, half8 (&af)[4]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const half8*>(a_lane + stage * (GM * GLD) + i * 32 * GLD + ks * 16);
-    };
     auto step = [&](const half8 (&af)[4], uint32_t nw0, uint32_t nw1) {
         const half8 n0v = unpack(nw0, 0), n1v = unpack(nw1, 1);
 #pragma unroll
@@ -360,59 +412,114 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
         bf[0] = n0v;
         bf[1] = n1v;
     };
-    auto interleave = [&](int ds_reads) {
-        if (ds_reads) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    auto interleave = [&]() {
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
     };
-
-    // Stage qt (64 channels = a quarter of a block) lives in LDS buffer qt & 1.  While it is
-    // multiplied, the activations and the weights of stage qt+1 are on their way; the scheduling
-    // fences keep the loads where they are written (the compiler would sink them next to their use
-    // and wait for them at once).
-    uint4 wcur[2], wnext[2];
-    uint32_t sc_next[2];
     half8 af0[4], af1[4];
-    load_x(0);
-    load_w(0, wcur, sc_next);
-    set_scale(sc_next);
-    bad |= hi0.x | hi0.y | hi1.x | hi1.y;
-    bf[0] = unpack(wcur[0].x, 0);
-    bf[1] = unpack(wcur[1].x, 1);
-    store_x(0);
-    __syncthreads();
-    for (int qt = 0; qt < QT; ++qt) {
-        const int stage = qt & 1;
-        load_x(qt + 1);
-        load_w(qt + 1, wnext, sc_next);
-        read_a(stage, 0, af0);
+    auto read_a = [&](uint32_t addr, half8 (&af)[4]) {
+        af[0] = lds_read_b128<0>(addr);
+        af[1] = lds_read_b128<4096>(addr);
+        af[2] = lds_read_b128<8192>(addr);
+        af[3] = lds_read_b128<12288>(addr);
+    };
+
+    // The loop is rotated by one MFMA step: a trip starts right after a barrier with the LAST step of
+    // the previous quarter (its fragments are already in registers), so that the matrix cores have
+    // work while the first fragment reads of the new quarter are on their way, then runs steps 0..2
+    // of its own quarter and ends with the barrier.  By then every wavefront has read the last
+    // fragments of the quarter (they sit in registers), so its buffer is free for the copies issued
+    // at the top of the next trip.
+    //   trip q:  copies X(q+2), W(q+3) | read A(q,0) | [step (q-1,3)] | read A(q,1), W(q+1) |
+    //            step (q,0) | read A(q,2) | step (q,1) | read A(q,3) | step (q,2) | waits, barrier
+    // kFirst: there is no previous quarter (bf already holds the operands of step (q,0)).
+    auto run_trip = [&](int q, int xr, auto first, const u32x4& c0, const u32x4& c1, u32x4& n0w, u32x4& n1w) {
+        constexpr bool kFirst = decltype(first)::value;
+        {
+            const int xd = xr == 0 ? 2 : xr - 1;  // (q + 2) % 3: held quarter q-1, all of whose reads completed before the barrier
+            copy_x(q + 2, xd);
+            copy_w(q + 3);  // that slot held quarter q-1, read by this wavefront a trip ago
+        }
+        const uint32_t wr = wread + (uint32_t)(((q + 1) & 3) * kWStageBytes), sr = sread + (uint32_t)(((q + 1) & 3) * kSStageBytes);
+        const uint32_t sb = (uint32_t)(xr * kXStageBytes);
         __builtin_amdgcn_sched_barrier(0);
-        read_a(stage, 1, af1);
-        step(af0, wcur[0].y, wcur[1].y);
-        interleave(1);
+        read_a(aoff[0] + sb, af0);
+        if constexpr (!kFirst) {
+            // last step of the previous quarter: fragments in af1 (read before the barrier); unpacks the
+            // first words of this quarter, whose scale was set a trip ago
+            step(af1, c0.x, c1.x);
+            interleave();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        n0w = lds_read_u4<0>(wr);
+        n1w = lds_read_u4<512>(wr);
+        uint32_t s0 = lds_read_b32<0>(sr), s1 = lds_read_b32<128>(sr);
+        read_a(aoff[1] + sb, af1);
+        asm volatile("s_waitcnt lgkmcnt(8)" : "+v"(af0[0]), "+v"(af0[1]), "+v"(af0[2]), "+v"(af0[3]));
+        step(af0, c0.y, c1.y);
+        interleave();
         __builtin_amdgcn_sched_barrier(0);
-        read_a(stage, 2, af0);
-        step(af1, wcur[0].z, wcur[1].z);
-        interleave(1);
+        read_a(aoff[2] + sb, af0);
+        asm volatile("s_waitcnt lgkmcnt(4)"
+                     : "+v"(af1[0]), "+v"(af1[1]), "+v"(af1[2]), "+v"(af1[3]), "+v"(n0w), "+v"(n1w), "+v"(s0), "+v"(s1));
+        step(af1, c0.z, c1.z);
+        interleave();
         __builtin_amdgcn_sched_barrier(0);
-        read_a(stage, 3, af1);
-        step(af0, wcur[0].w, wcur[1].w);
-        interleave(1);
+        read_a(aoff[3] + sb, af1);
+        ITQ3S_LDS_WAIT(4, af0);
+        step(af0, c0.w, c1.w);
+        interleave();
         __builtin_amdgcn_sched_barrier(0);
-        set_scale(sc_next);  // the next quarter may start a new block
-        bad |= hi0.x | hi0.y | hi1.x | hi1.y;
-        __builtin_amdgcn_sched_barrier(0);
-        step(af1, wnext[0].x, wnext[1].x);
-        interleave(0);
-        __builtin_amdgcn_sched_barrier(0);
-        store_x(stage ^ 1);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) wcur[j] = wnext[j];
-        __syncthreads();
+        set_scale(s0, s1);  // for the unpack of the next quarter's first words, at the top of the next trip
+        ITQ3S_LDS_WAIT(0, af1);
+        // Everything issued before this trip's six copies has landed: the activations of quarter q+1
+        // and the weights of quarter q+2 among them (copies complete in order).
+        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+    };
+
+    // Prologue: quarters 0 and 1 of everything and quarter 2 of the weights, in two groups of six
+    // copies, so that waiting for all but six leaves exactly the second group in flight.
+    u32x4 wa0, wa1, wb0, wb1;
+    copy_x(0, 0);
+    copy_w(0);
+    __builtin_amdgcn_sched_barrier(0);
+    copy_x(1, 1);
+    copy_w(1);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    copy_w(2);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+        wa0 = lds_read_u4<0>(wread);
+        wa1 = lds_read_u4<512>(wread);
+        uint32_t s0 = lds_read_b32<0>(sread), s1 = lds_read_b32<128>(sread);
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(wa0), "+v"(wa1), "+v"(s0), "+v"(s1));
+        set_scale(s0, s1);
+        bf[0] = unpack(wa0.x, 0);
+        bf[1] = unpack(wa1.x, 1);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(2)" ::: "memory");  // quarter 1 has landed as well; only the two copies of copy_w(2) may be in flight
+    __builtin_amdgcn_s_barrier();
+    // The two register sets of the weights alternate by name, so trips come in pairs: the first trip
+    // on its own, pairs (1,2), (3,4), ..., and the last trip (K is a multiple of 256: the number of
+    // quarters is a multiple of four, so it is odd-numbered).
+    run_trip(0, 0, std::true_type{}, wa0, wa1, wb0, wb1);
+    int xr = 1;
+    for (int q = 1; q + 1 < KT; q += 2) {
+        run_trip(q, xr, std::false_type{}, wb0, wb1, wa0, wa1);
+        xr = xr == 2 ? 0 : xr + 1;
+        run_trip(q + 1, xr, std::false_type{}, wa0, wa1, wb0, wb1);
+        xr = xr == 2 ? 0 : xr + 1;
+    }
+    run_trip(KT - 1, xr, std::false_type{}, wb0, wb1, wa0, wa1);
+    // last step of the last quarter (the words it unpacks are never used)
+    step(af1, wa0.x, wa1.x);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the look-ahead copies past the last quarter still target this workgroup's LDS
 
     // accumulator register v of a 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32
 #pragma unroll
@@ -431,14 +538,20 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
         }
     // zero-point term, only if a lane of this wavefront met one (columns past N read clamped rows and
     // may trigger it needlessly; nothing is stored for them)
-    if (__builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull) {
-#pragma unroll 1
-        for (int ij = 0; ij < 8; ++ij) {
-            const int i = ij >> 1, j = ij & 1;
-            subtract_zero_points(a, n0 + wn * 64 + j * 32 + l32, m0 + wm * 128 + i * 32, kg);
+    if (__builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull) subtract_zero_points_wave<128>(a, n0 + wn * 64, m0 + wm * 128, lane);
+    // Format check, outside the pipelined loop: the high plane of the workgroup's 16 tile rows must be
+    // zero (128 words per tile, a quarter of the packed bytes, read once more here).
+    if (a.flags != nullptr) {
+        const uint4* hp = reinterpret_cast<const uint4*>(a.codes + nt0 * a.KB * kTileWords);
+        const int64_t tiles = wg_tile_rows * a.KB;  // 32 pieces of 16 bytes per tile, at word 256 of each
+        uint32_t bad = 0;
+#pragma unroll 2
+        for (int64_t i = tid; i < tiles * 32; i += GT) {
+            const uint4 v = hp[(i >> 5) * (kTileWords / 4) + kTileLoWords / 4 + (i & 31)];
+            bad |= v.x | v.y | v.z | v.w;
         }
+        if (bad != 0u) atomicOr(a.flags, kFlagBadCode);
     }
-    if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
 }
 
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const _Float16* X, int64_t ldx,
@@ -448,16 +561,16 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
     a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
     const LaunchTiming tm = take_launch_timing();
     const int64_t tiles_m = (M + GM - 1) / GM, tiles_n = (N + GN - 1) / GN;
-    if (M >= kGemmBigMinM && tiles_m * tiles_n >= kGemmBigMinTiles && tiles_m * tiles_n < 0x7fffffff / 8) {
+    if (M >= kGemmBigMinM && tiles_m * tiles_n >= kGemmBigMinTiles && tiles_m * tiles_n < 0x7fffffff / 8 && K <= kGemmBigMaxK) {
         const int per = (int)((tiles_m * tiles_n + 7) / 8);
         const dim3 g((unsigned)(per * 8));
         static bool lds_limit_raised = false;
         if (!lds_limit_raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmBigLds) != hipSuccess) return -6;
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmDmaLds) != hipSuccess) return -6;
             lds_limit_raised = true;
         }
-        if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmBigLds, stream, tm.start, tm.stop, 0, a, (int)tiles_m, (int)tiles_n, per);
-        else hipLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmBigLds, stream, a, (int)tiles_m, (int)tiles_n, per);
+        if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmDmaLds, stream, tm.start, tm.stop, 0, a, (int)tiles_m, (int)tiles_n, per);
+        else hipLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmDmaLds, stream, a, (int)tiles_m, (int)tiles_n, per);
         return hipGetLastError() == hipSuccess ? 0 : -6;
     }
     dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
