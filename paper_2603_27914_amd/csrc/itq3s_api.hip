@@ -89,6 +89,7 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
     if (K <= 0 || M <= 0 || K % 256 != 0 || ldx < K) return ITQ3S_ERR_SHAPE;
     if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
     if (M > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
+    if (M > itq3s::kGemvMaxM && K > (1LL << 22)) return ITQ3S_ERR_SHAPE;  // the tiled kernel's 32-bit byte offsets
     int64_t n_max = 0;
     for (int i = 0; i < count; ++i) {
         if (!w[i].codes || !w[i].scales || !w[i].Y) return ITQ3S_ERR_NULL;

@@ -1,23 +1,20 @@
 // Tiled matmul for M > 16 activation rows (the prefill path): a dense contraction on the matrix
 // cores.  Alg. 2 dequantizes a weight tile into on-chip memory and multiplies from there; here the
-// tile written to LDS holds the un-rotated grid values d (q - z) in fp16 (exact for z = 0), the
-// rotation having been moved to the activations (Sec. 2.3: <H v, x> = <v, H x>), so the tile loader
-// needs two packed-fp16 operations per pair of weights and no butterflies.
+// operand fed to the matrix cores holds the un-rotated grid values d (q - z) in fp16 (exact for
+// z = 0), the rotation having been moved to the activations (Sec. 2.3: <H v, x> = <v, H x>), so the
+// weight path needs three packed-fp16 operations per pair of weights and no butterflies.
 //
 //   Y[m][n] = sum_k x~[m][k'] * g[n][k']  -  sum_b d z 16 x[m][256 b],   g = d (c - 1)  (exact in fp16)
 //
 // The zero-point multiplies the sum of the rotated chunk, and H 1 = 16 e_0 makes that sum exactly
 // 16 times the chunk's first element: the term is formed from the activations themselves in fp32.
 // Folding z into the fp16 operand instead would multiply the rounding errors of x~ by z.  The term
-// is rare (a fraction of a percent of the blocks on real weights), so the kernels note while they run
-// whether a zero-point came by and only then walk the scale words of their columns at the end.
+// is rare (a fraction of a percent of the blocks on real weights), so the kernel notes while it runs
+// whether a zero-point came by and only then walks the scale words of its columns at the end.
 //
 // k' is the channel order the unpack produces (within each group of 16 channels: 0,8,1,9,...,7,15);
-// the rotation kernel writes x~ in the same order, so both LDS tiles are plain [row][k'].
-//
-// Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 (m) x 128 (n) x 64 (k), wavefront tile 64 x 64
-// as 2 x 2 v_mfma_f32_32x32x16_f16.  A operand = x~ rows, B operand = weight rows, so a lane's
-// accumulator column is an output channel n and stores are contiguous along n.
+// the rotation kernel writes x~ in the same order.  A operand = x~ rows, B operand = weight rows, so
+// a lane's accumulator column is an output channel n and stores are contiguous along n.
 #include <hip/hip_ext.h>
 
 #include <type_traits>
@@ -27,12 +24,7 @@
 
 namespace itq3s {
 
-constexpr int BM = 128, BN = 128, BK = 64;
-// the 256 x 256 variant below takes over when there are enough rows to fill its tiles and enough
-// tiles to occupy the chip
-constexpr int kGemmBigMinM = 192, kGemmBigMinTiles = 128;
-constexpr int64_t kGemmBigMaxK = 1 << 21;  // its per-lane byte offsets (up to 256 rows x K x 2) are 32-bit
-constexpr int LDT = BK + 8;  // LDS row stride in halves (padding keeps 16-byte reads conflict-free)
+constexpr int64_t kGemmMaxK = 1 << 22;  // per-lane byte offsets (up to 128 rows x K x 2) are 32-bit
 
 struct GemmArgs {
     const uint32_t* codes;
@@ -92,153 +84,35 @@ __device__ __forceinline__ void subtract_zero_points_wave(const GemmArgs& a, int
     }
 }
 
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
-    __shared__ __align__(16) _Float16 As[BM * LDT];
-    __shared__ __align__(16) _Float16 Bs[BN * LDT];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;  // wavefront position in the 2 x 2 arrangement
-    const int64_t m0 = (int64_t)blockIdx.y * BM;
-    const int nt0 = blockIdx.x * (BN / 16);
-    const int KT = (int)(a.K / BK);
-
-    // weight loader role: 16-row tile tl, row r, half p of the 64-channel quarter
-    const int wp = tid & 1, wr = (tid >> 1) & 15, wtl = tid >> 5;
-    const bool w_ok = nt0 + wtl < a.NT;
-    // activation loader role: four 16-byte pieces per thread
-    uint4 xa[4];
-    uint2 wlo;
-    uint32_t whi = 0, wsc = 0, bad = 0, any_z = 0;
-
-    auto load_global = [&](int kt) {
-        const int b = kt >> 2, q = kt & 3;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i, row = idx >> 3, c16 = idx & 7;
-            const int64_t m = m0 + row;
-            xa[i] = m < a.M ? *reinterpret_cast<const uint4*>(a.Xt + m * a.K + (int64_t)kt * BK + c16 * 8) : make_uint4(0, 0, 0, 0);
-        }
-        if (w_ok) {
-            const int64_t tile = (int64_t)(nt0 + wtl) * a.KB + b;
-            const uint32_t* t = a.codes + tile * kTileWords;
-            const int ln = 16 * q + wr;
-            wlo = *reinterpret_cast<const uint2*>(t + 4 * ln + 2 * wp);
-            whi = t[kTileLoWords + 2 * ln + wp];
-            wsc = a.scales[tile * kTileRows + wr];
-        } else {
-            wlo = make_uint2(0x55555555u, 0x55555555u);
-            whi = 0;
-            wsc = 0;
-        }
-    };
-
-    auto store_lds = [&]() {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int idx = tid + 256 * i, row = idx >> 3, c16 = idx & 7;
-            *reinterpret_cast<uint4*>(&As[row * LDT + c16 * 8]) = xa[i];
-        }
-        bad |= whi;
-        any_z |= (wsc >> 16) & 0x7fffu;
-        // g = d * (c - 1): c * 2^-14 sits in bits 11:10 of each half after shift-and-mask
-        const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)(wsc & 0xffffu));
-        const half2v dd = {d, d};
-        const half2v k14 = {(_Float16)16384.0f, (_Float16)16384.0f};
-        const half2v off = {(_Float16)(-1.0f), (_Float16)(-1.0f)};
-        const uint32_t w2[2] = {wlo.x, wlo.y};
-        _Float16* dst = &Bs[(wtl * 16 + wr) * LDT + 32 * wp];
-#pragma unroll
-        for (int w = 0; w < 2; ++w) {
-            uint32_t o[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int sh = 10 - 2 * j;
-                const uint32_t bits = (sh >= 0 ? (w2[w] << sh) : (w2[w] >> (-sh))) & 0x0C000C00u;
-                half2v h = __builtin_bit_cast(half2v, bits);
-                h = (h * k14 + off) * dd;
-                o[j] = __builtin_bit_cast(uint32_t, h);
-            }
-            *reinterpret_cast<uint4*>(dst + 16 * w) = make_uint4(o[0], o[1], o[2], o[3]);
-            *reinterpret_cast<uint4*>(dst + 16 * w + 8) = make_uint4(o[4], o[5], o[6], o[7]);
-        }
-    };
-
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int l32 = lane & 31, kg = lane >> 5;
-    load_global(0);
-    for (int kt = 0; kt < KT; ++kt) {
-        __syncthreads();
-        store_lds();
-        __syncthreads();
-        if (kt + 1 < KT) load_global(kt + 1);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            half8 af[2], bf[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const half8*>(&As[(wm * 64 + i * 32 + l32) * LDT + ks * 16 + kg * 8]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const half8*>(&Bs[(wn * 64 + j * 32 + l32) * LDT + ks * 16 + kg * 8]);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-    }
-
-    // accumulator register v of a 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = (int64_t)nt0 * 16 + wn * 64 + j * 32 + l32;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                if (m < a.M && n < a.N) {
-                    if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[i][j][v];
-                    else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[i][j][v];
-                }
-            }
-        }
-    // zero-point term, only if some block of the workgroup's 128 rows has one
-    if (__syncthreads_or(any_z != 0u)) subtract_zero_points_wave<64>(a, (int64_t)nt0 * 16 + wn * 64, m0 + wm * 64, lane);
-    if (a.flags != nullptr && bad != 0u) atomicOr(a.flags, kFlagBadCode);
-}
-
 // ------------------------------------------------------------------------------------------------
-// Large-M variant: workgroup tile 256 (m) x 256 (n), eight wavefronts as 2 (m) x 4 (n), wavefront
-// tile 128 x 64 = 4 x 2 v_mfma_f32_32x32x16_f16 (128 accumulator registers per lane, two wavefronts
-// per SIMD so that one unpacks while the other multiplies), K in quarters of a block (64 channels =
-// four MFMA steps), one barrier per quarter.
+// Workgroup tile 128 (m) x 256 (n), four wavefronts side by side along n, wavefront tile 128 x 64 =
+// 4 x 2 v_mfma_f32_32x32x16_f16 (128 accumulator registers per lane), K in quarters of a block
+// (64 channels = four MFMA steps), one barrier per quarter.  Two workgroups share a compute unit
+// (68 KiB of LDS, about 220 registers), so every SIMD holds two wavefronts from different workgroups:
+// one unpacks while the other multiplies, and their barriers are not aligned.
+// (A 256 x 256 tile with eight wavefronts, one workgroup per compute unit, was measured too: within
+// 3 % where tiles are plentiful, up to 40 % slower where they are not.)
 //
 // A lane of the 32x32x16 product supplies, for its column n, eight consecutive channels k' of the
 // step -- and one low-plane word of the packed tile holds exactly the 16 channels of one step of one
 // row, in k' order after the unpack (pairs (slot j, slot j+8)).  So a lane needs, per quarter, the
 // four words (16 bytes) of each of its two rows, turns its half of a word into four half2 values
-// d (c - 1) in registers, and feeds the matrix core; no dequantized tile is ever stored.  The two
-// wavefronts that share a column range repeat that unpack.
+// d (c - 1) in registers, and feeds the matrix core; no dequantized tile is ever stored.
 //
 // Every operand is copied global -> LDS by the memory pipe itself (buffer_load ... lds: no registers,
 // no LDS store instructions), two to three quarters ahead of the arithmetic -- about 1.5 us of lead,
 // which covers an HBM miss.
 //
-// LDS (136 KiB):
-//   activations  ring of 3 quarters x 256 rows x 128 bytes, no padding (one copy instruction writes
+// LDS (68 KiB):
+//   activations  ring of 3 quarters x 128 rows x 128 bytes, no padding (one copy instruction writes
 //                1 KiB = 8 rows, lane l the 16-byte piece l of it).  To keep the 16-byte fragment
 //                reads conflict-free, piece p of row r holds channel chunk p ^ swz(r),
 //                swz(r) = (r & 7) ^ ((r >> 3) & 1): sixteen consecutive rows reading the same chunk
 //                touch sixteen different 16-byte groups of 256 bytes, eight rows eight groups of 128.
-//   weights      ring of 4 quarters x 8 wavefronts x 1 KiB: lane (l32, kg) copies the 16 bytes of ITS
+//   weights      ring of 4 quarters x 4 wavefronts x 1 KiB: lane (l32, kg) copies the 16 bytes of ITS
 //                row j = kg, and later reads both rows (its own piece and that of lane (l32, 1 - kg)).
 //                Private to the wavefront: ordered by the load counter alone, no barrier.
-//   scales       ring of 4 quarters x 8 wavefronts x 256 bytes, same pattern with 4 bytes per lane.
+//   scales       ring of 4 quarters x 4 wavefronts x 256 bytes, same pattern with 4 bytes per lane.
 // The weight ring runs one quarter further ahead than the activation ring because the last MFMA step
 // of a quarter already unpacks the first words of the next one.
 //
@@ -248,20 +122,21 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmArgs a) {
 // load-counter waits of its own inside the loop either; the explicit ones are all there are.
 //
 // Tile order: workgroups are dealt to the 8 chiplets round-robin by the hardware, so chiplet x takes
-// the contiguous run [x * per, (x+1) * per) of the tile list.  The list walks panels of two tile rows
-// (512 activation rows), inside a panel column by column: the 32 workgroups that run together on one
-// chiplet then cover 2 x 16 tiles and share, in that chiplet's L2, two activation slabs (the expensive
-// operand: 2 bytes per element) among sixteen workgroups each and sixteen weight slabs (0.39 bytes per
-// element) between two.
-constexpr int GM = 256, GN = 256, GK = 64;
-constexpr int GT = 512;  // threads
+// the contiguous run [x * per, (x+1) * per) of the tile list.  The list walks panels of four tile
+// rows (512 activation rows), inside a panel column by column: the workgroups that run together on
+// one chiplet then cover 4 x 16 tiles and share, in that chiplet's L2, four activation slabs (the
+// expensive operand: 2 bytes per element) among sixteen workgroups each and sixteen weight slabs
+// (0.39 bytes per element) among four.
+constexpr int GM = 128, GN = 256, GK = 64;
+constexpr int GT = 256;  // threads
 constexpr int kXStages = 3, kWStages = 4;
-constexpr int kXStageBytes = GM * GK * 2;                   // 32768
-constexpr int kWRingBase = kXStages * kXStageBytes;         // 98304
-constexpr int kWStageBytes = 8 * 1024;                      // 8 wavefronts x 64 lanes x 16 bytes
-constexpr int kSRingBase = kWRingBase + kWStages * kWStageBytes;  // 131072
-constexpr int kSStageBytes = 8 * 256;                       // 8 wavefronts x 64 lanes x 4 bytes
-constexpr int kGemmDmaLds = kSRingBase + kWStages * kSStageBytes;  // 139264
+constexpr int kXStageBytes = GM * GK * 2;                   // 16384
+constexpr int kWRingBase = kXStages * kXStageBytes;         // 49152
+constexpr int kWStageBytes = 4 * 1024;                      // 4 wavefronts x 64 lanes x 16 bytes
+constexpr int kSRingBase = kWRingBase + kWStages * kWStageBytes;  // 65536
+constexpr int kSStageBytes = 4 * 256;                       // 4 wavefronts x 64 lanes x 4 bytes
+constexpr int kGemmLds = kSRingBase + kWStages * kSStageBytes;    // 69632
+constexpr int kPanel = 4;                                   // tile rows per panel
 
 template <int OFF>
 __device__ __forceinline__ half8 lds_read_b128(uint32_t addr) {
@@ -285,20 +160,19 @@ __device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr) {
 // them can be scheduled ahead of the wait
 #define ITQ3S_LDS_WAIT(N, af) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(af[0]), "+v"(af[1]), "+v"(af[2]), "+v"(af[3]))
 
-__global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
+__global__ __launch_bounds__(GT) void gemm_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
     extern __shared__ __align__(1024) char lds[];
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int t = xcd * per_chiplet + slot;
     if (slot >= per_chiplet || t >= tiles_m * tiles_n) return;
-    constexpr int kPanel = 2;
     const int panel = t / (kPanel * tiles_n), within = t - panel * (kPanel * tiles_n);
     const int rows = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;
     const int tn = within / rows, tm = panel * kPanel + (within - tn * rows);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wn = wave;
     const int l32 = lane & 31, kg = lane >> 5;
     const int64_t m0 = (int64_t)tm * GM;
     const int64_t n0 = (int64_t)tn * GN;
@@ -353,13 +227,13 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
                                                  4, soff, b * (kTileRows * 4), 0, 0);
     };
 
-    // ---- fragment reads: row wm*128 + i*32 + l32, chunk 2 ks + kg, at position chunk ^ swz(row);
+    // ---- fragment reads: row i*32 + l32, chunk 2 ks + kg, at position chunk ^ swz(row);
     // swz depends on l32 only, so one byte offset per step ks serves all four i (+ 4096 i)
     uint32_t aoff[4];
     {
         const int s = (l32 & 7) ^ ((l32 >> 3) & 1);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) aoff[ks] = (uint32_t)((wm * 128 + l32) * 128 + (((2 * ks + kg) ^ s) * 16));
+        for (int ks = 0; ks < 4; ++ks) aoff[ks] = (uint32_t)(l32 * 128 + (((2 * ks + kg) ^ s) * 16));
     }
     const uint32_t wread = (uint32_t)(kWRingBase + 1024 * wave + 16 * l32);  // row 0 here, row 1 at + 512
     const uint32_t sread = (uint32_t)(kSRingBase + 256 * wave + 4 * l32);    // row 0 here, row 1 at + 128
@@ -529,7 +403,7 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
             const int64_t n = n0 + wn * 64 + j * 32 + l32;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const int64_t m = m0 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
                 if (m < a.M && n < a.N) {
                     if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[i][j][v];
                     else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[i][j][v];
@@ -538,10 +412,10 @@ __global__ __launch_bounds__(GT) void gemm_big_kernel(const GemmArgs a, int tile
         }
     // zero-point term, only if a lane of this wavefront met one (columns past N read clamped rows and
     // may trigger it needlessly; nothing is stored for them)
-    if (__builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull) subtract_zero_points_wave<128>(a, n0 + wn * 64, m0 + wm * 128, lane);
+    if (__builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull) subtract_zero_points_wave<128>(a, n0 + wn * 64, m0, lane);
     // Format check, outside the pipelined loop: the high plane of the workgroup's 16 tile rows must be
     // zero (128 words per tile, a quarter of the packed bytes, read once more here).
-    if (a.flags != nullptr) {
+    if (a.flags != nullptr && tm == 0) {  // once per tile column
         const uint4* hp = reinterpret_cast<const uint4*>(a.codes + nt0 * a.KB * kTileWords);
         const int64_t tiles = wg_tile_rows * a.KB;  // 32 pieces of 16 bytes per tile, at word 256 of each
         uint32_t bad = 0;
@@ -561,21 +435,16 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
     a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
     const LaunchTiming tm = take_launch_timing();
     const int64_t tiles_m = (M + GM - 1) / GM, tiles_n = (N + GN - 1) / GN;
-    if (M >= kGemmBigMinM && tiles_m * tiles_n >= kGemmBigMinTiles && tiles_m * tiles_n < 0x7fffffff / 8 && K <= kGemmBigMaxK) {
-        const int per = (int)((tiles_m * tiles_n + 7) / 8);
-        const dim3 g((unsigned)(per * 8));
-        static bool lds_limit_raised = false;
-        if (!lds_limit_raised) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_big_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmDmaLds) != hipSuccess) return -6;
-            lds_limit_raised = true;
-        }
-        if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmDmaLds, stream, tm.start, tm.stop, 0, a, (int)tiles_m, (int)tiles_n, per);
-        else hipLaunchKernelGGL(gemm_big_kernel, g, dim3(GT), kGemmDmaLds, stream, a, (int)tiles_m, (int)tiles_n, per);
-        return hipGetLastError() == hipSuccess ? 0 : -6;
+    if (K > kGemmMaxK || tiles_m * tiles_n >= 0x7fffffff / 8) return -2;
+    const int per = (int)((tiles_m * tiles_n + 7) / 8);
+    const dim3 g((unsigned)(per * 8));
+    static bool lds_limit_raised = false;
+    if (!lds_limit_raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds) != hipSuccess) return -6;
+        lds_limit_raised = true;
     }
-    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM));
-    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, tm.start, tm.stop, 0, a);
-    else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, stream, a);
+    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_kernel, g, dim3(GT), kGemmLds, stream, tm.start, tm.stop, 0, a, (int)tiles_m, (int)tiles_n, per);
+    else hipLaunchKernelGGL(gemm_kernel, g, dim3(GT), kGemmLds, stream, a, (int)tiles_m, (int)tiles_n, per);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
