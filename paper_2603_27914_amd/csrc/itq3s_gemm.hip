@@ -160,8 +160,11 @@ __device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr) {
 // them can be scheduled ahead of the wait
 #define ITQ3S_LDS_WAIT(N, af) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(af[0]), "+v"(af[1]), "+v"(af[2]), "+v"(af[3]))
 
-__global__ __launch_bounds__(GT) void gemm_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
+// (two wavefronts per SIMD: at most 256 registers)
+__global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
     extern __shared__ __align__(1024) char lds[];
+    // LDS byte address of the buffer, for the read instructions below that take raw addresses
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int t = xcd * per_chiplet + slot;
@@ -233,10 +236,10 @@ __global__ __launch_bounds__(GT) void gemm_kernel(const GemmArgs a, int tiles_m,
     {
         const int s = (l32 & 7) ^ ((l32 >> 3) & 1);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) aoff[ks] = (uint32_t)(l32 * 128 + (((2 * ks + kg) ^ s) * 16));
+        for (int ks = 0; ks < 4; ++ks) aoff[ks] = lds_base + (uint32_t)(l32 * 128 + (((2 * ks + kg) ^ s) * 16));
     }
-    const uint32_t wread = (uint32_t)(kWRingBase + 1024 * wave + 16 * l32);  // row 0 here, row 1 at + 512
-    const uint32_t sread = (uint32_t)(kSRingBase + 256 * wave + 4 * l32);    // row 0 here, row 1 at + 128
+    const uint32_t wread = lds_base + (uint32_t)(kWRingBase + 1024 * wave + 16 * l32);  // row 0 here, row 1 at + 512
+    const uint32_t sread = lds_base + (uint32_t)(kSRingBase + 256 * wave + 4 * l32);    // row 0 here, row 1 at + 128
 
     uint32_t any_z = 0;
     half2v dd[2];

@@ -429,6 +429,48 @@ def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("M,N,K", [(40, 300, 4096), (512, 384, 4096), (200, 1000, 8192), (300, 256, 2048), (1024, 512, 2048)])
+def test_matmul_few_tiles_long_k(gpu, ref, M, N, K):
+    """Few output tiles and a long K.  The workspace arrives full of garbage, is used three times in a
+    row without clearing, and every result equals the first bit for bit and the oracle within
+    tolerance; one block in a hundred has a zero-point."""
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "fewtiles", M, z_fraction=0.01)
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    X = synth.activations(M, K, "fewtiles", N)
+    Xd = to_dev(torch, X)
+    ws = torch.randint(0, 255, (binding.itq3s_matmul_workspace_bytes(M, N, K),), dtype=torch.uint8, device="cuda")
+    first = binding.itq3s_matmul(cd, sd, N, K, Xd, workspace=ws).clone()
+    for _ in range(2):
+        again = binding.itq3s_matmul(cd, sd, N, K, Xd, workspace=ws)
+        assert torch.equal(first, again)
+    half = binding.itq3s_matmul(cd, sd, N, K, Xd, dtype=torch.float16, workspace=ws)
+    torch.cuda.synchronize()
+    want = ref.matmul(codes, scales, N, K, X)
+    assert rel_rows(first.cpu().numpy(), want) <= MATMUL_TOL
+    assert rel_rows(half.cpu().numpy().astype(np.float64), want) <= MATMUL_TOL
+
+
+def test_matmul_tiled_shapes_share_a_workspace(gpu, ref):
+    """Tiled-path shapes with different tile counts follow each other on the same workspace with no
+    host synchronisation in between."""
+    torch, binding = gpu
+    cases = [(512, 384, 4096), (64, 2048, 1024), (300, 256, 2048), (17, 4096, 4096), (1024, 512, 2048), (512, 384, 4096)]
+    packed, xs = [], []
+    for i, (M, N, K) in enumerate(cases):
+        c, s = synth.random_packed(N, K, "tiled-ws", i)
+        packed.append((to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32))))
+        xs.append(to_dev(torch, synth.activations(M, K, "tiled-ws", i)))
+    alone = [binding.itq3s_matmul(*pk, N, K, x) for (M, N, K), pk, x in zip(cases, packed, xs)]
+    torch.cuda.synchronize()
+    ws = torch.randint(0, 255, (max(binding.itq3s_matmul_workspace_bytes(M, N, K) for M, N, K in cases),), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        outs = [binding.itq3s_matmul(*pk, N, K, x, workspace=ws) for (M, N, K), pk, x in zip(cases, packed, xs)]
+        torch.cuda.synchronize()
+        for a, b in zip(alone, outs):
+            assert torch.equal(a, b)
+
+
 def test_matmul_grouped_flags_and_determinism(gpu, ref):
     """The high-plane check covers every tensor of a grouped call; two identical calls give identical bits."""
     torch, binding = gpu
