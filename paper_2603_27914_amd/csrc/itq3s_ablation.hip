@@ -10,7 +10,7 @@
 //
 // A block is held by n/16 lanes, 16 consecutive elements each; a wavefront covers 1024 consecutive
 // channels of a row (64/(n/16) blocks at once).  Stages 1..8 stay in the lane, the longer ones
-// exchange with lane l^1, l^2, l^4, l^8 (moves inside a row of 16 lanes) and, for n = 512, l^16.
+// exchange with lane l^1, l^2, l^4, l^8 and, for n = 512, l^16 (swizzles through the LDS crossbar).
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 
@@ -20,20 +20,16 @@ constexpr double kAblTStar = 0.7979;  // optimal ternary scale / sigma (Sec. 3.3
 
 template <int MASK>
 __device__ __forceinline__ double abl_xor_f64(double v) {
-    if constexpr (MASK < 16) return row_xor_f64<MASK>(v);
-    else return xor_lane_f64(v, MASK);
+    return row_xor_f64<MASK>(v);
 }
 
 // butterfly stage across lanes: the lower lane of a pair gets u + v, the upper one (-v) + u = u - v
+// (one fused multiply-add with +-1: the product is exact)
 template <int MASK>
 __device__ __forceinline__ void abl_cross_stage(double (&a)[16], int lane) {
-    const int flip = (lane & MASK) ? (int)0x80000000u : 0;
+    const double sign = (lane & MASK) ? -1.0 : 1.0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const double p = abl_xor_f64<MASK>(a[i]);
-        const double s = __hiloint2double(__double2hiint(a[i]) ^ flip, __double2loint(a[i]));
-        a[i] = s + p;
-    }
+    for (int i = 0; i < 16; ++i) a[i] = __builtin_fma(a[i], sign, abl_xor_f64<MASK>(a[i]));  // (+-a) + p, one rounding
 }
 
 template <int L>  // lanes per block

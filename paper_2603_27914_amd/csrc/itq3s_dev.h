@@ -35,19 +35,13 @@ __device__ __forceinline__ double xor_lane_f64(double v, int mask) {
     return __hiloint2double(hi, lo);
 }
 
-// value of lane (l ^ MASK), MASK in {1, 2, 4, 8}: moves inside a row of 16 lanes
+// value of lane (l ^ MASK), MASK < 32, through the LDS crossbar (ds_swizzle in bit-mask mode: no
+// memory access).  One instruction per 32 bits for any distance, and it runs beside the vector ALU
+// rather than on it -- data-parallel-primitive moves need two per distance 4 or 8 and measured 12 %
+// slower in the fp64 butterfly kernels, which are bound by vector-ALU issue.
 template <int MASK>
 __device__ __forceinline__ int row_xor_i32(int x) {
-    // (every lane reads a valid lane, so no previous value of the destination is needed)
-    if constexpr (MASK == 1) return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true);       // quad_perm [1,0,3,2]
-    else if constexpr (MASK == 2) return __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
-    else if constexpr (MASK == 4) {  // l^7 (mirror in 8) then l^3 (reverse in 4)
-        x = __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true);
-        return __builtin_amdgcn_mov_dpp(x, 0x1B, 0xf, 0xf, true);
-    } else {  // l^15 (mirror in 16) then l^7
-        x = __builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true);
-        return __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true);
-    }
+    return __builtin_amdgcn_ds_swizzle(x, (MASK << 10) | 0x1F);
 }
 template <int MASK>
 __device__ __forceinline__ double row_xor_f64(double v) {

@@ -4,8 +4,8 @@
 // A block (256 consecutive channels of one row) is held by 16 lanes, 16 consecutive elements each:
 // a wavefront works on four rows of a storage tile at once, a workgroup of four wavefronts on the
 // whole 16-row tile.  Butterfly stages with distance 1, 2, 4, 8 stay inside the lane; distances
-// 16 .. 128 exchange with lane l^1, l^2, l^4, l^8 of the same row of 16 lanes, which are
-// data-parallel-primitive moves (no LDS traffic).  The 16 codes of a lane are exactly one low-plane
+// 16 .. 128 exchange with lane l^1, l^2, l^4, l^8 of the same row of 16 lanes through the LDS
+// crossbar (swizzles: no memory access).  The 16 codes of a lane are exactly one low-plane
 // word of the packed tile, so the result is stored straight from registers.  This file must be
 // compiled with floating point contraction off: every add, subtract and multiply below rounds on
 // its own.
@@ -17,16 +17,13 @@ namespace itq3s {
 constexpr double kTStar = 0.7979;  // optimal ternary scale / sigma (Sec. 3.3, App. A)
 
 // One cross-lane butterfly stage: the lower lane of a pair gets u + v, the upper one u - v (u the
-// lower lane's value).  The upper lane forms (-v) + u, which is u - v bit for bit.
+// lower lane's value).  Both are one fused multiply-add (+-1) * own + other: the product is exact,
+// so the upper lane's (-v) + u is u - v bit for bit.
 template <int MASK>
 __device__ __forceinline__ void cross_stage(double (&a)[16], int l16) {
-    const int flip = (l16 & MASK) ? (int)0x80000000u : 0;
+    const double sign = (l16 & MASK) ? -1.0 : 1.0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const double p = row_xor_f64<MASK>(a[i]);
-        const double s = __hiloint2double(__double2hiint(a[i]) ^ flip, __double2loint(a[i]));
-        a[i] = s + p;
-    }
+    for (int i = 0; i < 16; ++i) a[i] = __builtin_fma(a[i], sign, row_xor_f64<MASK>(a[i]));  // (+-a) + p, one rounding
 }
 
 // Sum over the 256 elements of a block, pairwise: neighbours first, then distance 2, 4, ... 128.
