@@ -89,6 +89,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
     ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
+    ap.add_argument("--prefill-m", default="512,2048", help="activation row counts of the prefill leg")
     ap.add_argument("--legs", default="per_shape,read_floor,stream70b,prefill,dequantize,ablation,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -237,7 +238,7 @@ def main():
     if "per_shape" in legs:
         out["per_shape"] = per_shape_leg(torch, binding, tensors, gen)
     if "prefill" in legs:
-        out["prefill"] = prefill_leg(torch, binding, synth, gen)
+        out["prefill"] = prefill_leg(torch, binding, synth, gen, [int(m) for m in args.prefill_m.split(",")])
     if "dequantize" in legs:
         out["dequantize"] = dequantize_leg(torch, binding, tensors)
     if "ablation" in legs:
@@ -312,14 +313,14 @@ def per_shape_leg(torch, binding, tensors, gen):
     return res
 
 
-def prefill_leg(torch, binding, synth, gen):
+def prefill_leg(torch, binding, synth, gen, m_list=(512, 2048)):
     """The MFMA path: X fp16 [M, K] times the two FFN-shaped tensors, M = 512 and 2048."""
     res = []
     for name, N, K in synth.SHAPES["prefill"]:
         W = student_t_weights(torch, gen, N, K)
         codes, scales = binding.itq3s_quantize(W)
         del W
-        for M in (512, 2048):
+        for M in m_list:
             X = activations(torch, gen, M, K)
             Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
             ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
