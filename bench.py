@@ -314,7 +314,9 @@ def per_shape_leg(torch, binding, tensors, gen):
 
 
 def prefill_leg(torch, binding, synth, gen, m_list=(512, 2048)):
-    """The MFMA path: X fp16 [M, K] times the two FFN-shaped tensors, M = 512 and 2048."""
+    """The MFMA path: X fp16 [M, K] times the two FFN-shaped tensors, M = 512 and 2048.  `us` / `TFLOPs`
+    are whole calls (rotation launch, contraction, and for shapes with few tiles the launch that adds
+    the split-K shares); `kernel_us` / `kernel_TFLOPs` the contraction launch alone."""
     res = []
     for name, N, K in synth.SHAPES["prefill"]:
         W = student_t_weights(torch, gen, N, K)

@@ -65,7 +65,9 @@ size_t itq3s_scales_bytes(int64_t N, int64_t K);
 
 /* Bytes of scratch itq3s_matmul needs for the rotated activations (Sec. 2.3: H is symmetric and
  * its own inverse, so <H v, x> = <v, H x>; the library rotates X once per call instead of every
- * weight block).  Never 0; grows with M*K. */
+ * weight block).  Never 0; grows with M*K.  For M > 16 and shapes with few output tiles (at most 128
+ * tiles of 128 x 256) it also covers the partial sums of the workgroups that share a tile's K range
+ * (up to 8 x M x N x 4 bytes, tiles rounded up). */
 size_t itq3s_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /* Offline quantization (Alg. 1, Def. 1).  Per block: w' = H w in fp64 (butterfly stages
@@ -157,7 +159,8 @@ int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block
 /* Measurement aids: itq3s_matmul / itq3s_matmul_grouped with the same arguments, after which the call
  * WAITS for the work and stores in *kernel_ms (HOST pointer) the duration of the contraction kernel
  * alone (the streaming kernel for M <= 16; for larger M the first tiled launch; not the
- * activation-rotation launch in front of it, not launch gaps), taken from HIP events attached to
+ * activation-rotation launch in front of it, not the launch that adds up partial sums behind it for
+ * shapes with few tiles, not launch gaps), taken from HIP events attached to
  * that kernel's dispatch.  They create and destroy two events per call and are not thread-safe: not
  * for production loops, not capturable in a graph. */
 int itq3s_matmul_timed(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,

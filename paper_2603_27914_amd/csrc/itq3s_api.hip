@@ -15,16 +15,20 @@ inline int pad_m(int64_t M) {
 }
 
 struct WorkspacePlan {
-    size_t xt_bytes, s_bytes, total;
+    size_t xt_bytes, s_bytes, flag_bytes, partial_bytes, total;
 };
 
-WorkspacePlan plan_workspace(int64_t M, int64_t K) {
+// N = the largest tensor of the call (sizes the split-K shares of the tiled path)
+WorkspacePlan plan_workspace(int64_t M, int64_t N, int64_t K) {
     WorkspacePlan p;
     const int64_t rows = M <= itq3s::kGemvMaxM ? pad_m(M) : M;
     p.xt_bytes = round_up((size_t)rows * (size_t)K * 2, 256);
     // streaming path without in-kernel rotation: two sums per (block, row), see launch_rotate_frag
     p.s_bytes = M <= itq3s::kGemvMaxM ? round_up((size_t)rows * (size_t)(K / 256) * 8, 256) : 0;
-    p.total = p.xt_bytes + p.s_bytes + 256;
+    // tiled path: split-K flags, then the shares (layout: rotated activations | flags | shares)
+    p.flag_bytes = M <= itq3s::kGemvMaxM ? 0 : 512;
+    p.partial_bytes = M <= itq3s::kGemvMaxM ? 0 : round_up(itq3s::gemm_partial_bytes(M, N, K), 256);
+    p.total = p.xt_bytes + p.s_bytes + p.flag_bytes + p.partial_bytes + 256;
     return p;
 }
 
@@ -43,9 +47,8 @@ size_t itq3s_scales_bytes(int64_t N, int64_t K) {
 }
 
 size_t itq3s_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-    (void)N;
-    if (M <= 0 || K <= 0 || K % 256 != 0) return 256;
-    return plan_workspace(M, K).total;
+    if (M <= 0 || N <= 0 || K <= 0 || K % 256 != 0) return 256;
+    return plan_workspace(M, N, K).total;
 }
 
 int itq3s_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* status_flags,
@@ -102,7 +105,7 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
     if (!aligned(workspace, 256)) return ITQ3S_ERR_ALIGN;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const WorkspacePlan p = plan_workspace(M, K);
+    const WorkspacePlan p = plan_workspace(M, n_max, K);
     _Float16* Xt = static_cast<_Float16*>(workspace);
     const _Float16* Xh = static_cast<const _Float16*>(X);
     const int y_f16 = y_dtype == ITQ3S_F16;
@@ -117,8 +120,18 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
         return itq3s::launch_gemv(gw, count, K, Xt, 0, S, M, MP, false, y_f16, status_flags, st);
     }
     // tiled path: one rotation, then one contraction launch per tensor
-    int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, st);
-    for (int i = 0; i < count && rc == 0; ++i) rc = itq3s::launch_gemm(w[i].codes, w[i].scales, w[i].N, K, Xt, Xh, ldx, M, w[i].Y, y_f16, w[i].ldy, status_flags, st);
+    unsigned char* const base = static_cast<unsigned char*>(workspace);
+    uint32_t* zflags = reinterpret_cast<uint32_t*>(base + p.xt_bytes);
+    float* partial = reinterpret_cast<float*>(base + p.xt_bytes + p.flag_bytes);
+    const size_t partial_room = workspace_bytes - p.xt_bytes - p.flag_bytes;  // (a tensor whose shares do not fit runs unsplit)
+    static_assert(itq3s::kGemmFlagWords * 4 <= 512, "flag words fit their slot");
+    int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, zflags, itq3s::kGemmFlagWords, st);
+    for (int i = 0; i < count && rc == 0; ++i) {
+        rc = itq3s::launch_gemm(w[i].codes, w[i].scales, w[i].N, K, Xt, Xh, ldx, M, w[i].Y, y_f16, w[i].ldy, partial, partial_room, zflags,
+                                status_flags, st);
+        // (the tensors of a group share the flag words: a flag left by an earlier tensor only costs the
+        // later one a needless scan of its scale words)
+    }
     return rc;
 }
 

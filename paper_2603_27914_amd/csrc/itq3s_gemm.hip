@@ -35,6 +35,11 @@ struct GemmArgs {
     uint32_t* flags;
     int64_t N, K, M, ldy, ldx;
     int NT, KB, y_f16;
+    // split-K (splits > 1): the contraction kernel writes partial tiles [tile][split][32][256 threads]
+    // of four floats and ORs 1 into zflags[tile] if it met a zero-point; a second launch adds them up
+    float* partial;
+    uint32_t* zflags;
+    int splits;
 };
 
 // Zero-point term of a wavefront's output block that has already been stored: columns
@@ -68,7 +73,7 @@ __device__ __forceinline__ void subtract_zero_points_wave(const GemmArgs& a, int
 #pragma unroll 1
                 for (int r = 0; r < MROWS; r += kWave) {
                     const int64_t m = m_first + r + lane;
-                    if (m < a.M) {
+                    if (m < a.M && r + lane < MROWS) {
                         const float t = dz * (16.0f * (float)a.X[m * a.ldx + (int64_t)(b0 + u) * kBlock]);
                         if (a.y_f16) {
                             _Float16* y = reinterpret_cast<_Float16*>(a.Y) + m * a.ldy + nh;
@@ -160,6 +165,42 @@ __device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr) {
 // them can be scheduled ahead of the wait
 #define ITQ3S_LDS_WAIT(N, af) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(af[0]), "+v"(af[1]), "+v"(af[2]), "+v"(af[3]))
 
+// Position of tile t in the walk described above.
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int panel = t / (kPanel * tiles_n), within = t - panel * (kPanel * tiles_n);
+    const int rows = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;  // the last panel may be short
+    tn = within / rows;
+    tm = panel * kPanel + (within - tn * rows);
+}
+
+// Store 32 rows (m_first ..) of a wavefront's 64 columns (n0 + 64 wn ..).  Accumulator register v of a
+// 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32.
+__device__ __forceinline__ void store_rows(const GemmArgs& a, const floatx16 (&acc)[2], int64_t m_first, int64_t n0, int wn, int lane) {
+    const int l32 = lane & 31, kg = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t n = n0 + wn * 64 + j * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t m = m_first + 8 * (v >> 2) + 4 * kg + (v & 3);
+            if (m < a.M && n < a.N) {
+                if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[j][v];
+                else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[j][v];
+            }
+        }
+    }
+}
+
+// Store a wavefront's 128 x 64 block (rows m0.., columns n0 + 64 wn ..) and apply the zero-point term
+// if one was met (columns past N read clamped rows and may trigger it needlessly; nothing is stored
+// for them).
+__device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&acc)[4][2], int64_t m0, int64_t n0, int wn, int lane,
+                                           bool zero_points) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) store_rows(a, acc[i], m0 + i * 32, n0, wn, lane);
+    if (zero_points) subtract_zero_points_wave<128>(a, n0 + wn * 64, m0, lane);
+}
+
 // (two wavefronts per SIMD: at most 256 registers)
 __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_kernel(const GemmArgs a, int tiles_m, int tiles_n, int per_chiplet) {
     extern __shared__ __align__(1024) char lds[];
@@ -167,11 +208,12 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int t = xcd * per_chiplet + slot;
-    if (slot >= per_chiplet || t >= tiles_m * tiles_n) return;
-    const int panel = t / (kPanel * tiles_n), within = t - panel * (kPanel * tiles_n);
-    const int rows = tiles_m - panel * kPanel < kPanel ? tiles_m - panel * kPanel : kPanel;
-    const int tn = within / rows, tm = panel * kPanel + (within - tn * rows);
+    const int item = xcd * per_chiplet + slot;
+    if (slot >= per_chiplet || item >= tiles_m * tiles_n * a.splits) return;
+    // the splits of a tile are neighbours in the list
+    const int t = item / a.splits, split = item - t * a.splits;
+    int tm, tn;
+    tile_coords(t, tiles_m, tiles_n, tm, tn);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -180,6 +222,8 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const int64_t m0 = (int64_t)tm * GM;
     const int64_t n0 = (int64_t)tn * GN;
     const int KT = (int)(a.K / GK);
+    // this workgroup's share of K: whole blocks, quarters q0 .. q1 - 1
+    const int q0 = 4 * (int)((int64_t)split * a.KB / a.splits), q1 = 4 * (int)((int64_t)(split + 1) * a.KB / a.splits);
 
     // All copies go through buffer descriptors: a 32-bit per-lane offset fixed for the whole kernel
     // plus a scalar offset that advances with the stage -- no address arithmetic in the vector pipe.
@@ -361,14 +405,14 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     // Prologue: quarters 0 and 1 of everything and quarter 2 of the weights, in two groups of six
     // copies, so that waiting for all but six leaves exactly the second group in flight.
     u32x4 wa0, wa1, wb0, wb1;
-    copy_x(0, 0);
-    copy_w(0);
+    copy_x(q0, 0);
+    copy_w(q0);
     __builtin_amdgcn_sched_barrier(0);
-    copy_x(1, 1);
-    copy_w(1);
+    copy_x(q0 + 1, 1);
+    copy_w(q0 + 1);
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    copy_w(2);
+    copy_w(q0 + 2);
     __builtin_amdgcn_sched_barrier(0);
     {
         wa0 = lds_read_u4<0>(wread);
@@ -385,40 +429,22 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     // The two register sets of the weights alternate by name, so trips come in pairs: the first trip
     // on its own, pairs (1,2), (3,4), ..., and the last trip (K is a multiple of 256: the number of
     // quarters is a multiple of four, so it is odd-numbered).
-    run_trip(0, 0, std::true_type{}, wa0, wa1, wb0, wb1);
+    run_trip(q0, 0, std::true_type{}, wa0, wa1, wb0, wb1);
     int xr = 1;
-    for (int q = 1; q + 1 < KT; q += 2) {
+    for (int q = q0 + 1; q + 1 < q1; q += 2) {
         run_trip(q, xr, std::false_type{}, wb0, wb1, wa0, wa1);
         xr = xr == 2 ? 0 : xr + 1;
         run_trip(q + 1, xr, std::false_type{}, wa0, wa1, wb0, wb1);
         xr = xr == 2 ? 0 : xr + 1;
     }
-    run_trip(KT - 1, xr, std::false_type{}, wb0, wb1, wa0, wa1);
+    run_trip(q1 - 1, xr, std::false_type{}, wb0, wb1, wa0, wa1);
     // last step of the last quarter (the words it unpacks are never used)
     step(af1, wa0.x, wa1.x);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the look-ahead copies past the last quarter still target this workgroup's LDS
 
-    // accumulator register v of a 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t n = n0 + wn * 64 + j * 32 + l32;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                if (m < a.M && n < a.N) {
-                    if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[i][j][v];
-                    else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[i][j][v];
-                }
-            }
-        }
-    // zero-point term, only if a lane of this wavefront met one (columns past N read clamped rows and
-    // may trigger it needlessly; nothing is stored for them)
-    if (__builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull) subtract_zero_points_wave<128>(a, n0 + wn * 64, m0, lane);
-    // Format check, outside the pipelined loop: the high plane of the workgroup's 16 tile rows must be
+    // Format check, apart from the arithmetic: the high plane of the workgroup's 16 tile rows must be
     // zero (128 words per tile, a quarter of the packed bytes, read once more here).
-    if (a.flags != nullptr && tm == 0) {  // once per tile column
+    if (a.flags != nullptr && tm == 0 && split == 0) {  // once per tile column
         const uint4* hp = reinterpret_cast<const uint4*>(a.codes + nt0 * a.KB * kTileWords);
         const int64_t tiles = wg_tile_rows * a.KB;  // 32 pieces of 16 bytes per tile, at word 256 of each
         uint32_t bad = 0;
@@ -429,17 +455,80 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         }
         if (bad != 0u) atomicOr(a.flags, kFlagBadCode);
     }
+    const bool zero_points = __builtin_amdgcn_ballot_w64(any_z != 0u) != 0ull;  // did a lane of this wavefront meet one?
+    if (a.splits > 1) {
+        // split-K: park the sums; the launch that follows adds the shares of every tile in split order
+        floatx4* const mine = reinterpret_cast<floatx4*>(a.partial) + ((int64_t)(t * a.splits + split) * 32) * GT + tid;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    mine[((i * 2 + j) * 4 + c) * GT] = floatx4{acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2], acc[i][j][4 * c + 3]};
+        if (zero_points && lane == 0) atomicOr(a.zflags + t, 1u);
+        return;
+    }
+    store_tile(a, acc, m0, n0, wn, lane, zero_points);
+}
+
+// Second launch of a split-K matmul: four workgroups per tile, one per 32-row slab, add the shares
+// in split order (thread and register layout as in the contraction kernel) and finish the slab.
+__global__ __launch_bounds__(GT) void gemm_reduce_kernel(const GemmArgs a, int tiles_m, int tiles_n) {
+    const int t = (int)(blockIdx.x >> 2), i = (int)(blockIdx.x & 3), tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
+    int tm, tn;
+    tile_coords(t, tiles_m, tiles_n, tm, tn);
+    const floatx4* const all = reinterpret_cast<const floatx4*>(a.partial) + ((int64_t)t * a.splits * 32) * GT + tid;
+    floatx16 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int piece = (i * 2 + j) * 4 + c;
+            floatx4 share[kGemmMaxSplits];  // all loads first (absent splits re-read share 0), then the sum in split order
+#pragma unroll
+            for (int sp = 0; sp < kGemmMaxSplits; ++sp) share[sp] = all[((int64_t)(sp < a.splits ? sp : 0) * 32 + piece) * GT];
+            floatx4 sum = share[0];
+#pragma unroll
+            for (int sp = 1; sp < kGemmMaxSplits; ++sp)
+                if (sp < a.splits) sum = sum + share[sp];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[j][4 * c + e] = sum[e];
+        }
+    const int64_t m_first = (int64_t)tm * GM + i * 32, n0 = (int64_t)tn * GN;
+    store_rows(a, acc, m_first, n0, wn, lane);
+    if (a.zflags[t] != 0u) subtract_zero_points_wave<32>(a, n0 + wn * 64, m_first, lane);
+}
+
+// Splits of K per tile: when the tiles alone leave three quarters of the chip idle, enough workgroups
+// for its 512 slots (two per compute unit), each split at least four blocks long.  A function of the
+// shape only.
+int gemm_splits(int64_t M, int64_t N, int64_t K) {
+    const int64_t tiles = ((M + GM - 1) / GM) * ((N + GN - 1) / GN);
+    if (tiles > kGemmSplitMaxTiles) return 1;
+    int64_t s = 512 / tiles;
+    if (s > kGemmMaxSplits) s = kGemmMaxSplits;
+    if (s > K / kBlock / 4) s = K / kBlock / 4;
+    return s < 1 ? 1 : (int)s;
+}
+size_t gemm_partial_bytes(int64_t M, int64_t N, int64_t K) {
+    const int s = gemm_splits(M, N, K);
+    return s > 1 ? (size_t)s * (size_t)(((M + GM - 1) / GM) * ((N + GN - 1) / GN)) * (GM * GN * 4) : 0;
 }
 
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const _Float16* X, int64_t ldx,
-                int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
+                int64_t M, void* Y, int y_f16, int64_t ldy, float* partial, size_t partial_bytes, uint32_t* zflags, uint32_t* flags,
+                hipStream_t stream) {
     GemmArgs a;
     a.codes = codes; a.scales = scales; a.Xt = Xt; a.X = X; a.ldx = ldx; a.Y = Y; a.flags = flags;
     a.N = N; a.K = K; a.M = M; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
+    a.partial = partial; a.zflags = zflags;
+    // split only if the caller's workspace has room for the shares (a grouped call sizes it for its largest tensor)
+    a.splits = partial != nullptr && zflags != nullptr && gemm_partial_bytes(M, N, K) <= partial_bytes ? gemm_splits(M, N, K) : 1;
     const LaunchTiming tm = take_launch_timing();
     const int64_t tiles_m = (M + GM - 1) / GM, tiles_n = (N + GN - 1) / GN;
-    if (K > kGemmMaxK || tiles_m * tiles_n >= 0x7fffffff / 8) return -2;
-    const int per = (int)((tiles_m * tiles_n + 7) / 8);
+    if (K > kGemmMaxK || tiles_m * tiles_n >= 0x7fffffff / 8 / kGemmMaxSplits) return -2;
+    const int per = (int)((tiles_m * tiles_n * a.splits + 7) / 8);
     const dim3 g((unsigned)(per * 8));
     static bool lds_limit_raised = false;
     if (!lds_limit_raised) {
@@ -448,7 +537,12 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
     }
     if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_kernel, g, dim3(GT), kGemmLds, stream, tm.start, tm.stop, 0, a, (int)tiles_m, (int)tiles_n, per);
     else hipLaunchKernelGGL(gemm_kernel, g, dim3(GT), kGemmLds, stream, a, (int)tiles_m, (int)tiles_n, per);
-    return hipGetLastError() == hipSuccess ? 0 : -6;
+    if (hipGetLastError() != hipSuccess) return -6;
+    if (a.splits > 1) {
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)(tiles_m * tiles_n * 4)), dim3(GT), 0, stream, a, (int)tiles_m, (int)tiles_n);
+        if (hipGetLastError() != hipSuccess) return -6;
+    }
+    return 0;
 }
 
 }  // namespace itq3s

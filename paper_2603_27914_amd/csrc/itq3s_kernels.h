@@ -36,7 +36,8 @@ int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, 
 int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, hipStream_t stream);
 
 // Rotated activations for the tiled path: Xt[m][k] row-major, row stride K.
-int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, hipStream_t stream);
+// (also clears n_zero words at zero_words: the split-K flags of the contraction that follows)
+int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, uint32_t* zero_words, int n_zero, hipStream_t stream);
 
 // True if the streaming kernel can rotate the activations itself (one launch, no workspace use).
 bool gemv_can_fuse(int64_t M, int64_t K);
@@ -56,9 +57,19 @@ struct GemvWeight {
 int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
                 int y_f16, uint32_t* flags, hipStream_t stream);
 
-// Xt = rotated activations (launch_rotate_rowmajor); X, ldx = the activations themselves (zero-point term).
+// Tiled matmul, M > 16.  Xt = rotated activations (launch_rotate_rowmajor); X, ldx = the activations
+// themselves (zero-point term).  Shapes with few output tiles split K over several workgroups per tile
+// and add the shares in a second launch (gemm_splits > 1): those use `partial` (gemm_partial_bytes,
+// 16-byte aligned; partial_bytes = what is there -- too little, or none, means no split) and
+// `zflags` (kGemmFlagWords words, all zero at launch).
+constexpr int kGemmMaxSplits = 8;
+constexpr int kGemmSplitMaxTiles = 128;  // more tiles than this: no split
+constexpr int kGemmFlagWords = 128;
+int gemm_splits(int64_t M, int64_t N, int64_t K);
+size_t gemm_partial_bytes(int64_t M, int64_t N, int64_t K);
 int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* Xt, const _Float16* X, int64_t ldx,
-                int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+                int64_t M, void* Y, int y_f16, int64_t ldy, float* partial, size_t partial_bytes, uint32_t* zflags, uint32_t* flags,
+                hipStream_t stream);
 
 // Tiled matmul with the inverse transform applied to the weights inside the tile loader (Alg. 2 as
 // printed); X = the activations themselves.  Any M.

@@ -78,9 +78,12 @@ __global__ __launch_bounds__(256) void rotate_frag_kernel(const _Float16* __rest
 // Operand order of the tiled kernel: rows stay rows; inside every group of 16 channels, slot s moves
 // to position 2 (s & 7) + (s >> 3), the order in which the tile loader's unpack emits the weights.
 __global__ __launch_bounds__(256) void rotate_rowmajor_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
-                                                              _Float16* __restrict__ Xt) {
+                                                              _Float16* __restrict__ Xt, uint32_t* __restrict__ zero_words, int n_zero) {
     const int64_t KB = K / kBlock;
     const int lane = lane_id();
+    // the split-K flags of the contraction that follows start from zero
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < n_zero; i += 256) zero_words[i] = 0u;
     const int64_t chunk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (chunk >= M * KB) return;
     const int64_t m = chunk / KB, b = chunk - m * KB;
@@ -100,9 +103,9 @@ int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, hipStream_t stream) {
+int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, uint32_t* zero_words, int n_zero, hipStream_t stream) {
     const int64_t chunks = M * (K / kBlock);
-    hipLaunchKernelGGL(rotate_rowmajor_kernel, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, stream, X, M, K, ldx, Xt);
+    hipLaunchKernelGGL(rotate_rowmajor_kernel, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, stream, X, M, K, ldx, Xt, zero_words, n_zero);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
