@@ -214,7 +214,7 @@ def test_matmul_small_m(gpu, ref, M, N, K):
     assert run_matmul(torch, binding, ref, codes, scales, N, K, X) <= MATMUL_TOL
 
 
-@pytest.mark.parametrize("M,N,K", [(17, 48, 512), (64, 256, 1024), (130, 1000, 768), (200, 144, 2048), (512, 384, 4096)])
+@pytest.mark.parametrize("M,N,K", [(40, 100, 256), (17, 48, 512), (64, 256, 1024), (130, 1000, 768), (200, 144, 2048), (512, 384, 4096), (129, 257, 1280)])
 def test_matmul_tiled_path(gpu, ref, M, N, K):
     torch, binding = gpu
     codes, scales = synth.random_packed(N, K, "gemm", M, z_fraction=0.02)
