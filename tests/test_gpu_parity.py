@@ -567,8 +567,10 @@ def test_matmul_full_size_sampled_rows(gpu, ref, name, N, K, Ms):
         assert worst <= MATMUL_TOL, (N, K, M, worst)
 
 
-@pytest.mark.parametrize("N,K,M", [(14336, 4096, 512), (4096, 14336, 512), (14336, 4096, 2048)])
+@pytest.mark.parametrize("N,K,M", [(14336, 4096, 512), (4096, 14336, 512), (14336, 4096, 2048), (4096, 4096, 2048), (3700, 512, 1100), (4100, 768, 1000)])
 def test_matmul_prefill_full_size_sampled(gpu, ref, N, K, M):
+    """The benchmark's prefill shapes and a few with 129..256 tiles (one workgroup per compute unit):
+    sampled activation rows and weight-row ranges against the oracle, first and last tile included."""
     torch, binding = gpu
     codes, scales = synth.random_packed(N, K, "prefill", z_fraction=0.001)
     X = synth.activations(M, K, "prefill", N)
