@@ -17,8 +17,11 @@
 
 namespace itq3s {
 
+// (at least two wavefronts per SIMD: with a register budget of 256 the matrix instructions write ordinary
+// vector registers; with the full 512 the compiler parks their results in accumulator registers and copies
+// every one of them out)
 template <bool kOutF16>
-__global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scales,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void dequantize_kernel(const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scales,
                                                          int64_t N, int KB, void* __restrict__ out, int64_t ldo,
                                                          uint32_t* __restrict__ flags) {
     const int tile = (int)blockIdx.x;
@@ -44,31 +47,38 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
         hi[rr] = *reinterpret_cast<const u32x2*>(t + kTileLoWords + 2 * (16 * g + r));
         sw[rr] = scales[(int64_t)tile * kTileRows + r];
     }
-    bool bad = false;
+    uint32_t bad = 0;
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int r = wave * 4 + rr;
         const int64_t n = (int64_t)nt * kTileRows + r;
         if (n >= N) break;
-        const uint32_t lw[4] = {lo[rr].x, lo[rr].y, lo[rr].z, lo[rr].w};
-        const uint32_t hw[2] = {hi[rr].x, hi[rr].y};
-        half4 v;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t c = ((lw[j] >> (2 * r16)) & 3u) | (((hw[j >> 1] >> (16 * (j & 1) + r16)) & 1u) << 2);
-            bad |= c > 2u;
-            v[j] = (_Float16)(float)((int)c - 1);
+        // The lane's four codes sit in slot r16 of the four low-plane words.  Two at a time they are
+        // OR-ed into the mantissa of the half 1024.0, whose lowest mantissa bit weighs exactly 1:
+        // 1024 + c, minus 1025, is the digit c - 1 (exact).  A code 3, or any high-plane bit of the
+        // row (every lane of the row group reads the same words), is a format error.
+        const uint32_t sh = 2u * (uint32_t)r16;
+        const uint32_t c0 = (lo[rr].x >> sh) & 3u, c1 = (lo[rr].y >> sh) & 3u, c2 = (lo[rr].z >> sh) & 3u, c3 = (lo[rr].w >> sh) & 3u;
+        uint32_t p01 = c0 | (c1 << 16), p23 = c2 | (c3 << 16);
+        bad |= (((p01 & (p01 >> 1)) | (p23 & (p23 >> 1))) & 0x00010001u) | hi[rr].x | hi[rr].y;
+        if (__builtin_amdgcn_ballot_w64((hi[rr].x | hi[rr].y) != 0u) != 0ull) {
+            // (malformed input only) the high bits count 4: the digit is still code - 1
+            p01 |= (((hi[rr].x >> r16) & 1u) << 2) | (((hi[rr].x >> (16 + r16)) & 1u) << 18);
+            p23 |= (((hi[rr].y >> r16) & 1u) << 2) | (((hi[rr].y >> (16 + r16)) & 1u) << 18);
         }
+        const half2v bias = {(_Float16)(-1025.0f), (_Float16)(-1025.0f)};
+        const half2v v01 = __builtin_bit_cast(half2v, p01 | 0x64006400u) + bias, v23 = __builtin_bit_cast(half2v, p23 | 0x64006400u) + bias;
+        const half4 v = {v01[0], v01[1], v23[0], v23[1]};
         const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
         const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(v, h, zero, 0, 0, 0);  // V^T H_16, |.| <= 16 * 6
         const half4 th = {(_Float16)T[0], (_Float16)T[1], (_Float16)T[2], (_Float16)T[3]};
         const floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);
-        const float d = f16_bits_to_f32(sw[rr] & 0xffffu);
+        const float d16 = f16_bits_to_f32(sw[rr] & 0xffffu) * 0.0625f;  // d / 16: exact, so one rounding per output as before
         const float z = f16_bits_to_f32(sw[rr] >> 16);
         float f[4] = {U[0], U[1], U[2], U[3]};
         if (lane == 0) f[0] = f[0] - 256.0f * z;  // H_u applied to the constant -z
 #pragma unroll
-        for (int i = 0; i < 4; ++i) f[i] = (d * f[i]) * 0.0625f;
+        for (int i = 0; i < 4; ++i) f[i] = d16 * f[i];
         const int64_t off = n * ldo + (int64_t)b * kBlock + 16 * r16 + 4 * g;
         if (kOutF16) {
             half4 o = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
@@ -77,7 +87,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* __restr
             *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + off) = make_float4(f[0], f[1], f[2], f[3]);
         }
     }
-    if (flags != nullptr && __builtin_amdgcn_ballot_w64(bad) != 0ull && lane == 0) atomicOr(flags, kFlagBadCode);
+    if (flags != nullptr && __builtin_amdgcn_ballot_w64(bad != 0u) != 0ull && lane == 0) atomicOr(flags, kFlagBadCode);
 }
 
 int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* out, int out_f16, int64_t ldo,

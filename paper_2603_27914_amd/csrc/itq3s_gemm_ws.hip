@@ -36,7 +36,10 @@ struct GemmWsArgs {
     int NT, KB, y_f16;
 };
 
-__global__ __launch_bounds__(256) void gemm_ws_kernel(const GemmWsArgs a) {
+// (at least two wavefronts per SIMD: with a register budget of 256 the matrix instructions write ordinary
+// vector registers; with the full 512 the compiler parks their results in accumulator registers and copies
+// every one of them out)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void gemm_ws_kernel(const GemmWsArgs a) {
     extern __shared__ __align__(16) _Float16 lds[];
     _Float16* const As = lds;             // [WM][WLD] activations
     _Float16* const Bs = lds + WM * WLD;  // [WN][WLD] reconstructed weights

@@ -48,7 +48,10 @@ __device__ __forceinline__ void rotate_chunk(const _Float16* __restrict__ src, i
 // of the chunk, which is where the weight kernel's shift-and-mask unpack puts the code of the same
 // element.  Xt index = (((b*8 + t)*4 + g)*MP + m)*8 + i.   S[b*MP + m] = sum_e x~_e (rounded values),
 // S[KB*MP + b*MP + m] = 16 x_0 (the same sum before rounding, exact).
-__global__ __launch_bounds__(256) void rotate_frag_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx, int MP,
+// (at least two wavefronts per SIMD: with a register budget of 256 the matrix instructions write ordinary
+// vector registers; with the full 512 the compiler parks their results in accumulator registers and copies
+// every one of them out)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void rotate_frag_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx, int MP,
                                                           _Float16* __restrict__ Xt, float* __restrict__ S) {
     const int64_t KB = K / kBlock;
     const int lane = lane_id();
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(256) void rotate_frag_kernel(const _Float16* __rest
 
 // Operand order of the tiled kernel: rows stay rows; inside every group of 16 channels, slot s moves
 // to position 2 (s & 7) + (s >> 3), the order in which the tile loader's unpack emits the weights.
-__global__ __launch_bounds__(256) void rotate_rowmajor_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void rotate_rowmajor_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
                                                               _Float16* __restrict__ Xt, uint32_t* __restrict__ zero_words, int n_zero) {
     const int64_t KB = K / kBlock;
     const int lane = lane_id();
