@@ -51,8 +51,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int r = wave * 4 + rr;
-        const int64_t n = (int64_t)nt * kTileRows + r;
-        if (n >= N) break;
+        const int64_t n = (int64_t)nt * kTileRows + r;  // (rows past N exist in storage; only their store is skipped)
         // The lane's four codes sit in slot r16 of the four low-plane words.  Two at a time they are
         // OR-ed into the mantissa of the half 1024.0, whose lowest mantissa bit weighs exactly 1:
         // 1024 + c, minus 1025, is the digit c - 1 (exact).  A code 3, or any high-plane bit of the
@@ -80,11 +79,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
 #pragma unroll
         for (int i = 0; i < 4; ++i) f[i] = d16 * f[i];
         const int64_t off = n * ldo + (int64_t)b * kBlock + 16 * r16 + 4 * g;
-        if (kOutF16) {
-            half4 o = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
-            *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(out) + off) = o;
-        } else {
-            *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + off) = make_float4(f[0], f[1], f[2], f[3]);
+        if (n < N) {
+            if (kOutF16) {
+                half4 o = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
+                *reinterpret_cast<half4*>(reinterpret_cast<_Float16*>(out) + off) = o;
+            } else {
+                *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + off) = make_float4(f[0], f[1], f[2], f[3]);
+            }
         }
     }
     if (flags != nullptr && __builtin_amdgcn_ballot_w64(bad != 0u) != 0ull && lane == 0) atomicOr(flags, kFlagBadCode);
