@@ -90,9 +90,9 @@ int itq3s_dequantize(const uint32_t *codes, const uint32_t *scales, int64_t N, i
                      int64_t ldo, uint32_t *status_flags, void *stream);
 
 /* Fused matmul (problem statement of Alg. 2; Sec. 5.4 for M = 1):  Y[m][n] = sum_k X[m][k] w_hat[n][k].
- * No dequantized weight is written to memory.  M <= 16 takes the bandwidth-bound streaming path,
- * larger M the tiled MFMA path (which accepts K <= 4194304 only: ITQ3S_ERR_SHAPE beyond); fp32
- * accumulation in both.
+ * No dequantized weight is written to memory.  M <= 16 takes the bandwidth-bound streaming path
+ * (M <= 32: two passes of it), larger M the tiled MFMA path (which accepts K <= 4194304 only:
+ * ITQ3S_ERR_SHAPE beyond); fp32 accumulation in both.
  *   X  [in]  device, M x K fp16 row-major, row stride ldx elements (ldx >= K, ldx % 8 == 0,
  *            pointer 16-byte aligned)
  *   Y  [out] device, M x N of y_dtype, row stride ldy elements (ldy >= N); overwritten
@@ -158,7 +158,7 @@ int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block
 
 /* Measurement aids: itq3s_matmul / itq3s_matmul_grouped with the same arguments, after which the call
  * WAITS for the work and stores in *kernel_ms (HOST pointer) the duration of the contraction kernel
- * alone (the streaming kernel for M <= 16; for larger M the first tiled launch; not the
+ * alone (the streaming kernel for M <= 16, its first pass for M <= 32; for larger M the first tiled launch; not the
  * activation-rotation launch in front of it, not the launch that adds up partial sums behind it for
  * shapes with few tiles, not launch gaps), taken from HIP events attached to
  * that kernel's dispatch.  They create and destroy two events per call and are not thread-safe: not

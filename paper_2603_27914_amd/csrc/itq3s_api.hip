@@ -19,7 +19,10 @@ struct WorkspacePlan {
 };
 
 // N = the largest tensor of the call (sizes the split-K shares of the tiled path)
+constexpr int64_t kChunkedMaxM = 2 * itq3s::kGemvMaxM;  // up to here M > 16 runs as passes of the streaming kernel
+
 WorkspacePlan plan_workspace(int64_t M, int64_t N, int64_t K) {
+    if (M > itq3s::kGemvMaxM && M <= kChunkedMaxM) return plan_workspace(itq3s::kGemvMaxM, N, K);
     WorkspacePlan p;
     const int64_t rows = M <= itq3s::kGemvMaxM ? pad_m(M) : M;
     p.xt_bytes = round_up((size_t)rows * (size_t)K * 2, 256);
@@ -105,6 +108,23 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
     if (!aligned(workspace, 256)) return ITQ3S_ERR_ALIGN;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M > itq3s::kGemvMaxM && M <= kChunkedMaxM) {
+        // A few rows more than the streaming kernel takes at once: two passes of it over the weights
+        // are still faster than the tiled kernel, whose 128-row tiles would be mostly empty.
+        const size_t y_bytes = y_dtype == ITQ3S_F16 ? 2 : 4;
+        for (int64_t m0 = 0; m0 < M; m0 += itq3s::kGemvMaxM) {
+            itq3s_weight part[ITQ3S_MAX_GROUP];
+            for (int i = 0; i < count; ++i) {
+                part[i] = w[i];
+                part[i].Y = static_cast<unsigned char*>(w[i].Y) + (size_t)m0 * (size_t)w[i].ldy * y_bytes;
+            }
+            const int64_t rows = M - m0 < itq3s::kGemvMaxM ? M - m0 : itq3s::kGemvMaxM;
+            const int rc = itq3s_matmul_grouped(part, count, K, static_cast<const _Float16*>(X) + m0 * ldx, rows, ldx, y_dtype, workspace,
+                                                workspace_bytes, status_flags, stream);
+            if (rc != 0) return rc;
+        }
+        return ITQ3S_OK;
+    }
     const WorkspacePlan p = plan_workspace(M, n_max, K);
     _Float16* Xt = static_cast<_Float16*>(workspace);
     const _Float16* Xh = static_cast<const _Float16*>(X);

@@ -199,7 +199,7 @@ def run_matmul(torch, binding, ref, codes, scales, N, K, X, out_dtype=None, rows
     return worst
 
 
-@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16, 17, 25, 32])  # 17..32: two passes of the streaming kernel
 @pytest.mark.parametrize("N,K", [(16, 256), (48, 512), (1000, 1024), (2048, 2048), (272, 11008)])
 def test_matmul_small_m(gpu, ref, M, N, K):
     torch, binding = gpu
