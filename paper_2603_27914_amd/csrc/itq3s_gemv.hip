@@ -353,7 +353,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         for (int d = 0; d < (D > NBX ? D : NBX); ++d) {
             if (d < D) issue(ring[d], d);
             __builtin_amdgcn_sched_barrier(0);
-            if (d < NBX) rotate_slot(d);
+            if (d < NBX && d < nb) rotate_slot(d);  // (slots past the list hold block 0 again: nothing to rotate)
             __builtin_amdgcn_sched_barrier(0);
         }
     } else {
