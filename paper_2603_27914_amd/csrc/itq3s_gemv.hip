@@ -361,21 +361,31 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         for (int d = 0; d < D; ++d) issue(ring[d], d);
     }
 
-    // ---- steady state: NB steps per trip, every prefetch is a live step
-    int bi = 0;
-    for (; bi + NB + D <= nb; bi += NB) {
+    if (kFused && NBX <= 4 && D <= NBX && nb == NBX) {
+        // The wavefront's list fills its slots exactly (K = 2048 NBX: 4096, 8192): a fixed schedule with
+        // no stand-in loads behind the last step.
 #pragma unroll
-        for (int k = 0; k < NB; ++k) {
-            issue(ring[(k + D) % NB], bi + k + D);
-            compute(ring[k], bi + k);
+        for (int j = 0; j < NBX; ++j) {
+            if (j + D < NBX) issue(ring[(j + D) % NB], j + D);
+            compute(ring[j % NB], j);
         }
-    }
-    // ---- tail: fewer than NB + D steps left
+    } else {
+        // ---- steady state: NB steps per trip, every prefetch is a live step
+        int bi = 0;
+        for (; bi + NB + D <= nb; bi += NB) {
 #pragma unroll
-    for (int k = 0; k < NB + D - 1; ++k) {
-        if (bi + k >= nb) break;  // straight line up to the exit: no merge point between steps
-        issue(ring[(k + D) % NB], bi + k + D);
-        compute(ring[k % NB], bi + k);
+            for (int k = 0; k < NB; ++k) {
+                issue(ring[(k + D) % NB], bi + k + D);
+                compute(ring[k], bi + k);
+            }
+        }
+        // ---- tail: fewer than NB + D steps left
+#pragma unroll
+        for (int k = 0; k < NB + D - 1; ++k) {
+            if (bi + k >= nb) break;  // straight line up to the exit: no merge point between steps
+            issue(ring[(k + D) % NB], bi + k + D);
+            compute(ring[k % NB], bi + k);
+        }
     }
 
     // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]; slot_out says where
