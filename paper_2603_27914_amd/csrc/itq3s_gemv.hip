@@ -39,8 +39,10 @@ namespace itq3s {
 
 constexpr int kGemvWaves = 8;        // wavefronts per workgroup
 constexpr int kGemvMaxRT = 7;        // row tiles per workgroup, at most
-constexpr int kFusedMaxBlocks = 16;  // fused rotation: blocks per wavefront times MP, at most (bounds the
-                                     // registers and the LDS the rotated activations take)
+// fused rotation: blocks per wavefront times MP, at most (bounds the registers and the LDS the rotated
+// activations take, and the time every workgroup spends rotating the same activations)
+// (32 for 8 and 16 rows was measured: slower than the separate rotation launch)
+constexpr int fused_max_blocks(int) { return 16; }
 
 static LaunchTiming g_timing;
 void set_launch_timing(hipEvent_t start, hipEvent_t stop) { g_timing.start = start; g_timing.stop = stop; }
@@ -151,8 +153,8 @@ struct HadamardOperand {
 };
 
 // x~ = H x for one 256-chunk, rounded to fp16, scattered into operand order at `dst` (256*MP halves:
-// index ((t*4 + g)*MP + m)*8 + i); returns the sum of the rounded values in every lane.
-template <int MP>
+// index ((t*4 + g)*MP + m)*8 + i); kSum: returns the sum of the rounded values in every lane.
+template <int MP, bool kSum>
 __device__ __forceinline__ float rotate_to_lds(u32x2 raw, const HadamardOperand& H, int lane, int m, _Float16* dst) {
     const half4 xa = __builtin_bit_cast(half4, raw);
     const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -168,8 +170,11 @@ __device__ __forceinline__ float rotate_to_lds(u32x2 raw, const HadamardOperand&
     _Float16 r[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) r[i] = (_Float16)(U[i] * 0.25f);
-    float s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
-    s += lane_xor<1>(s); s += lane_xor<2>(s); s += lane_xor<4>(s); s += lane_xor<8>(s); s += lane_xor<16>(s); s += lane_xor<32>(s);
+    float s = 0.f;
+    if constexpr (kSum) {
+        s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
+        s += lane_xor<1>(s); s += lane_xor<2>(s); s += lane_xor<4>(s); s += lane_xor<8>(s); s += lane_xor<16>(s); s += lane_xor<32>(s);
+    }
     // element e = 64g + 16w + slot (w = r, slot = l%16): quarter g, low-plane word w, code slot `slot`;
     // MFMA step t = 2w + ((slot&7)>>2), position i = 2(slot&3) + (slot>>3)
     const int g = lane >> 4, slot = lane & 15;
@@ -179,12 +184,17 @@ __device__ __forceinline__ float rotate_to_lds(u32x2 raw, const HadamardOperand&
     return s;
 }
 
-// NBX = 0: direct; NBX > 0: fused, with room for NBX blocks per wavefront (NBX * MP <= kFusedMaxBlocks).
+// NBX = 0: direct; NBX > 0: fused, with room for NBX blocks per wavefront (NBX * MP <= fused_max_blocks(MP)).
 // kGrouped: the launch serves several tensors (a single-tensor launch skips the lookup and the
 // fetch of the unused descriptors, which are on the way to the first load).
 template <int MP, int RT, int D, int NBX, bool kGrouped>
 __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a) {
     constexpr bool kFused = NBX > 0;
+    // Several activation rows: the block sums S come from the matrix cores (the same fragments against an
+    // operand of all ones, eight instructions per block on an otherwise idle pipe) instead of one
+    // cross-lane sum per rotated chunk, and the rotations of a slot are straight-line code whose
+    // dependent chains overlap.  One row: the cross-lane sum is cheaper (measured).
+    constexpr bool kMfmaSum = MP >= 2;
     constexpr int W = kGemvWaves;
     constexpr int NB = D + 1;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -243,6 +253,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     float* ss = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * 512) + wave * NBX * MP * 2;
     float* se = ss + NBX * MP;
     float* red = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * (512 + 8));  // W*RT*MP*16 floats
+    float* spare = reinterpret_cast<float*>(smem + (size_t)W * NBX * MP * (512 + 8) + (size_t)W * RT * MP * 16 * 4 + (size_t)RT * 32) + wave * 64;
 
     floatx4 acc[RT];
 #pragma unroll
@@ -290,7 +301,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
             for (int t = 0; t < 8; ++t) Xf[t] = *reinterpret_cast<const half8*>(xb + ((t * 4 + g) * MP + mm) * 8);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
+                if constexpr (!kMfmaSum) sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
                 ev[i] = se[j * MP + ((4 * g + i) & (MP - 1))];
             }
         } else {
@@ -298,6 +309,14 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
             for (int t = 0; t < 8; ++t) Xf[t] = s.xf[t];
             sv = s.sv;
             ev = s.ev;
+        }
+        if constexpr (kFused && kMfmaSum) {
+            floatx4 sacc = {0.f, 0.f, 0.f, 0.f};
+            const half8 ones = as_half8(0x04000400u, 0x04000400u, 0x04000400u, 0x04000400u);  // 2^-14 each
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf[t], ones, sacc, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * 16384.0f;
         }
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -341,11 +360,16 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
             for (int m = 0; m < MP; ++m) {
                 u32x2 raw = xraw[j * MP + m];
                 if (m >= a.M) raw = u32x2{0u, 0u};
-                const float s = rotate_to_lds<MP>(raw, H, lane, m, xs + (size_t)j * MP * 256);
-                if (lane == 0) {
+                const float s = rotate_to_lds<MP, !kMfmaSum>(raw, H, lane, m, xs + (size_t)j * MP * 256);
+                // lane 0 holds x[0..3] of the chunk: E = 16 x_0
+                const float e = 16.0f * (float)__builtin_bit_cast(_Float16, (uint16_t)(raw.x & 0xffffu));
+                if constexpr (kMfmaSum) {
+                    // no branch between the rotations of a slot: the other lanes write to a spare word each
+                    float* dst = lane == 0 ? &se[j * MP + m] : &spare[lane];
+                    *dst = e;
+                } else if (lane == 0) {
                     ss[j * MP + m] = s;
-                    // lane 0 holds x[0..3] of the chunk: E = 16 x_0
-                    se[j * MP + m] = 16.0f * (float)__builtin_bit_cast(_Float16, (uint16_t)(raw.x & 0xffffu));
+                    se[j * MP + m] = e;
                 }
             }
         };
@@ -421,7 +445,7 @@ static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
         lds_limit_raised = true;
     }
-    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 8) + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
+    const size_t lds = (size_t)kGemvWaves * NBX * MP * (512 + 8) + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32 + (size_t)kGemvWaves * 256;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
@@ -464,11 +488,11 @@ static int launch_nbx(const GemvArgs& a, int grid, int nb_max, hipStream_t strea
         if (nb_max <= 2) {
             if constexpr (D <= 2) return launch_one<MP, RT, D, 2>(a, grid, stream);
         } else if (nb_max <= 4) {
-            if constexpr (4 * MP <= kFusedMaxBlocks && D <= 4) return launch_one<MP, RT, D, 4>(a, grid, stream);
+            if constexpr (4 * MP <= fused_max_blocks(MP) && D <= 4) return launch_one<MP, RT, D, 4>(a, grid, stream);
         } else if (nb_max <= 8) {
-            if constexpr (8 * MP <= kFusedMaxBlocks && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 8>(a, grid, stream);
+            if constexpr (8 * MP <= fused_max_blocks(MP) && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 8>(a, grid, stream);
         } else {
-            if constexpr (16 * MP <= kFusedMaxBlocks && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 16>(a, grid, stream);
+            if constexpr (16 * MP <= fused_max_blocks(MP) && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 16>(a, grid, stream);
         }
         return -6;
     }
@@ -504,7 +528,7 @@ bool gemv_can_fuse(int64_t M, int64_t K) {
     int mp = 1;
     while (mp < M) mp <<= 1;
     const int64_t nb_max = (K / kBlock + kGemvWaves - 1) / kGemvWaves;
-    return mp <= 4 && nb_max * mp <= kFusedMaxBlocks;
+    return mp <= 8 && nb_max * mp <= fused_max_blocks(mp);
 }
 
 int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
@@ -531,18 +555,29 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
         t.pad_ = 0;
     }
     if (nt_total >= 0x7fffffff) return -2;
+    const int nb_min = a.KB / kGemvWaves, nb_max = (a.KB + kGemvWaves - 1) / kGemvWaves;
+    // row tiles per workgroup, at most: the register ring's limit, and with many fused rows what the LDS
+    // leaves next to the rotated activations (8 NBX MP 520 bytes; 8 MP 64 bytes of partial sums per tile)
+    int max_rt = kGemvMaxRT;
+    if (fused) {
+        const int nbx = nb_max <= 2 ? 2 : nb_max <= 4 ? 4 : nb_max <= 8 ? 8 : 16;
+        const int64_t room = 160 * 1024 - 4096 - (int64_t)kGemvWaves * nbx * MP * (512 + 8);
+        const int64_t fit = room / ((int64_t)kGemvWaves * MP * 64 + 32);
+        if (fit < 1) return -2;
+        if (fit < max_rt) max_rt = (int)fit;
+    }
     int64_t grid64 = nt_total < cu_count() ? nt_total : cu_count();
-    if ((nt_total + grid64 - 1) / grid64 > kGemvMaxRT) grid64 = (nt_total + kGemvMaxRT - 1) / kGemvMaxRT;
+    if ((nt_total + grid64 - 1) / grid64 > max_rt) grid64 = (nt_total + max_rt - 1) / max_rt;
     const int grid = (int)grid64;
     const int rt = (int)((nt_total + grid - 1) / grid);
     a.nt_q = (int)(nt_total / grid);
     a.nt_r = (int)(nt_total % grid);
-    const int nb_min = a.KB / kGemvWaves, nb_max = (a.KB + kGemvWaves - 1) / kGemvWaves;
     if (fused) {
         switch (MP) {
             case 1: return launch_shape<1, true>(a, grid, rt, nb_min, nb_max, stream);
             case 2: return launch_shape<2, true>(a, grid, rt, nb_min, nb_max, stream);
             case 4: return launch_shape<4, true>(a, grid, rt, nb_min, nb_max, stream);
+            case 8: return launch_shape<8, true>(a, grid, rt, nb_min, nb_max, stream);
         }
         return -2;
     }
