@@ -290,6 +290,7 @@ GROUPS = [
     (11008, [4096, 40], (1, 3)),                 # long K (rotation launch for M = 3), a tensor with 3 row tiles
     (512, [16, 1000, 17, 300], (1, 5)),          # four ragged tensors, one with a single row tile
     (1024, [200, 48], (33,)),                    # tiled path
+    (2048, [300, 48, 1000], (20, 32, 300)),      # two passes of the streaming kernel; tiled path with split K and without
 ]
 
 
