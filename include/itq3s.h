@@ -14,6 +14,9 @@
  *     on the host before anything is launched; then no kernel runs and no memory is touched.
  *   - `status_flags` (may be NULL) is one device uint32 into which kernels OR data-condition bits
  *     (ITQ3S_FLAG_*); the caller clears and reads it.
+ *   - calls may come from several host threads at once: the library keeps no mutable state apart
+ *     from cached device properties.  Calls that share a workspace or an output must be ordered by
+ *     the caller (same stream, or events).
  *   - K must be a multiple of 256 (the paper leaves other widths open, Sec. 8).  N is arbitrary;
  *     storage is padded to a multiple of 16 rows.
  *
@@ -161,8 +164,8 @@ int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block
  * alone (the streaming kernel for M <= 16, its first pass for M <= 32; for larger M the first tiled launch; not the
  * activation-rotation launch in front of it, not the launch that adds up partial sums behind it for
  * shapes with few tiles, not launch gaps), taken from HIP events attached to
- * that kernel's dispatch.  They create and destroy two events per call and are not thread-safe: not
- * for production loops, not capturable in a graph. */
+ * that kernel's dispatch.  They create and destroy two events per call: not for production loops,
+ * not capturable in a graph. */
 int itq3s_matmul_timed(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
                        int64_t ldx, void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes,
                        uint32_t *status_flags, void *stream, float *kernel_ms);

@@ -12,6 +12,8 @@
 // channels of a row (64/(n/16) blocks at once).  Stages 1..8 stay in the lane, the longer ones
 // exchange with lane l^1, l^2, l^4, l^8 and, for n = 512, l^16 (swizzles through the LDS crossbar).
 #include "itq3s_dev.h"
+#include <atomic>
+
 #include "itq3s_kernels.h"
 
 namespace itq3s {
@@ -204,11 +206,13 @@ __global__ __launch_bounds__(256) void roundtrip_kernel(const AblArgs a) {
 }
 
 static int compute_units() {
-    static int n = 0;
+    static std::atomic<int> n_cached{0};
+    int n = n_cached.load(std::memory_order_relaxed);
     if (n == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
         else n = 256;
+        n_cached.store(n, std::memory_order_relaxed);
     }
     return n;
 }
@@ -217,11 +221,13 @@ static int compute_units() {
 // unit), each wavefront walking over its share of the (row, chunk) pairs.
 template <int L>
 static int launch_roundtrip_n(const AblArgs& a, hipStream_t stream) {
-    static int per_cu = 0;
+    static std::atomic<int> per_cu_cached{0};
+    int per_cu = per_cu_cached.load(std::memory_order_relaxed);
     if (per_cu == 0) {
         int v = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, roundtrip_kernel<L>, 256, 0) != hipSuccess || v < 1) v = 2;
         per_cu = v;
+        per_cu_cached.store(v, std::memory_order_relaxed);
     }
     const int64_t wgs = (a.N * a.chunks + 3) / 4, cap = (int64_t)per_cu * compute_units();
     hipLaunchKernelGGL(roundtrip_kernel<L>, dim3((unsigned)(wgs < cap ? wgs : cap)), dim3(256), 0, stream, a);

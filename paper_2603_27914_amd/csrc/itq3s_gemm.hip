@@ -20,6 +20,8 @@
 #include <type_traits>
 
 #include "itq3s_dev.h"
+#include <atomic>
+
 #include "itq3s_kernels.h"
 
 namespace itq3s {
@@ -530,7 +532,7 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
     if (K > kGemmMaxK || tiles_m * tiles_n >= 0x7fffffff / 8 / kGemmMaxSplits) return -2;
     const int per = (int)((tiles_m * tiles_n * a.splits + 7) / 8);
     const dim3 g((unsigned)(per * 8));
-    static bool lds_limit_raised = false;
+    static std::atomic<bool> lds_limit_raised{false};
     if (!lds_limit_raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds) != hipSuccess) return -6;
         lds_limit_raised = true;

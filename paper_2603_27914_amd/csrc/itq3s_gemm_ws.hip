@@ -18,6 +18,8 @@
 #include <hip/hip_ext.h>
 
 #include "itq3s_dev.h"
+#include <atomic>
+
 #include "itq3s_kernels.h"
 
 namespace itq3s {
@@ -150,7 +152,7 @@ int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, int64
     GemmWsArgs a;
     a.codes = codes; a.scales = scales; a.X = X; a.Y = Y; a.flags = flags;
     a.N = N; a.M = M; a.ldx = ldx; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
-    static bool lds_limit_raised = false;
+    static std::atomic<bool> lds_limit_raised{false};
     if (!lds_limit_raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ws_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmWsLds) != hipSuccess) return -6;
         lds_limit_raised = true;

@@ -33,6 +33,8 @@
 #include <hip/hip_ext.h>
 
 #include "itq3s_dev.h"
+#include <atomic>
+
 #include "itq3s_kernels.h"
 
 namespace itq3s {
@@ -44,7 +46,7 @@ constexpr int kGemvMaxRT = 7;        // row tiles per workgroup, at most
 // (32 for 8 and 16 rows was measured: slower than the separate rotation launch)
 constexpr int fused_max_blocks(int) { return 16; }
 
-static LaunchTiming g_timing;
+static thread_local LaunchTiming g_timing;  // armed and taken on the calling thread
 void set_launch_timing(hipEvent_t start, hipEvent_t stop) { g_timing.start = start; g_timing.stop = stop; }
 LaunchTiming take_launch_timing() {
     const LaunchTiming t = g_timing;
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
 template <int MP, int RT, int D, int NBX, bool kGrouped>
 static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
     auto kern = gemv_kernel<MP, RT, D, NBX, kGrouped>;
-    static bool lds_limit_raised = false;  // once per instantiation: allow up to the 160 KB of a CU
+    static std::atomic<bool> lds_limit_raised{false};  // once per instantiation: allow up to the 160 KB of a CU
     if (!lds_limit_raised) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) return -6;
         lds_limit_raised = true;
@@ -459,11 +461,13 @@ static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
 }
 
 static int cu_count() {
-    static int n = 0;
+    static std::atomic<int> n_cached{0};
+    int n = n_cached.load(std::memory_order_relaxed);
     if (n == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
         else n = 256;
+        n_cached.store(n, std::memory_order_relaxed);
     }
     return n;
 }

@@ -430,6 +430,50 @@ def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
             assert torch.equal(a, b)
 
 
+def test_matmul_from_two_host_threads(gpu, ref):
+    """Two host threads call the library at the same time, each with its own workspace and outputs
+    (streaming, two-pass and tiled shapes, one thread through the timed entry point): every result
+    equals the one computed alone, bit for bit."""
+    import threading
+
+    torch, binding = gpu
+    cases = [(1, 1000, 4096), (8, 272, 4096), (20, 512, 1024), (200, 300, 2048), (3, 4096, 11008)]
+    packed, xs = [], []
+    for i, (M, N, K) in enumerate(cases):
+        c, s = synth.random_packed(N, K, "threads", i)
+        packed.append((to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32))))
+        xs.append(to_dev(torch, synth.activations(M, K, "threads", i)))
+    alone = [binding.itq3s_matmul(*p, N, K, x) for (M, N, K), p, x in zip(cases, packed, xs)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(timed):
+        try:
+            torch.cuda.set_device(0)
+            ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for M, N, K in cases), dtype=torch.uint8, device="cuda")
+            for _ in range(10):
+                outs = []
+                for (M, N, K), p, x in zip(cases, packed, xs):
+                    if timed:
+                        y, ms = binding.itq3s_matmul_timed(*p, N, K, x, workspace=ws)
+                        assert ms > 0.0
+                    else:
+                        y = binding.itq3s_matmul(*p, N, K, x, workspace=ws)
+                    outs.append(y)
+                torch.cuda.synchronize()
+                for a, b in zip(alone, outs):
+                    assert torch.equal(a, b)
+        except BaseException as e:  # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in (False, True)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 @pytest.mark.parametrize("M,N,K", [(40, 300, 4096), (512, 384, 4096), (200, 1000, 8192), (300, 256, 2048), (1024, 512, 2048)])
 def test_matmul_few_tiles_long_k(gpu, ref, M, N, K):
     """Few output tiles and a long K.  The workspace arrives full of garbage, is used three times in a
