@@ -43,8 +43,9 @@ constexpr int kGemvWaves = 8;        // wavefronts per workgroup
 constexpr int kGemvMaxRT = 7;        // row tiles per workgroup, at most
 // fused rotation: blocks per wavefront times MP, at most (bounds the registers and the LDS the rotated
 // activations take, and the time every workgroup spends rotating the same activations)
-// (32 for 8 and 16 rows was measured: slower than the separate rotation launch)
-constexpr int fused_max_blocks(int) { return 16; }
+// (32 for 8 and 16 rows was measured: slower than the separate rotation launch; for 2 to 4 rows it
+// wins on long K: 4096x11008 at M = 4 12.0 -> 10.5 us, 8192x28672 at M = 2 28.2 -> 24.4 us)
+constexpr int fused_max_blocks(int mp) { return mp <= 4 ? 32 : 16; }
 
 static thread_local LaunchTiming g_timing;  // armed and taken on the calling thread
 void set_launch_timing(hipEvent_t start, hipEvent_t stop) { g_timing.start = start; g_timing.stop = stop; }

@@ -200,7 +200,7 @@ def run_matmul(torch, binding, ref, codes, scales, N, K, X, out_dtype=None, rows
 
 
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16, 17, 25, 32])  # 17..32: two passes of the streaming kernel
-@pytest.mark.parametrize("N,K", [(16, 256), (48, 512), (1000, 1024), (2048, 2048), (272, 11008)])
+@pytest.mark.parametrize("N,K", [(16, 256), (48, 512), (1000, 1024), (2048, 2048), (272, 11008), (100, 20480)])
 def test_matmul_small_m(gpu, ref, M, N, K):
     torch, binding = gpu
     if (N, K) == (2048, 2048):
@@ -592,10 +592,10 @@ def sample_row_ranges(N, count, seed):
 FULL = [
     ("llama7b", 4096, 4096, (1, 8)),
     ("llama7b", 11008, 4096, (1, 8)),
-    ("llama7b", 4096, 11008, (1, 8)),
+    ("llama7b", 4096, 11008, (1, 4, 8)),
     ("llama70b", 8192, 8192, (1, 4, 16)),
-    ("llama70b", 28672, 8192, (1, 16)),
-    ("llama70b", 8192, 28672, (1, 16)),
+    ("llama70b", 28672, 8192, (1, 4, 16)),
+    ("llama70b", 8192, 28672, (1, 2, 16)),
     ("llama70b", 1024, 8192, (1, 4, 16)),
 ]
 
