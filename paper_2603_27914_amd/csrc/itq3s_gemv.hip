@@ -496,10 +496,10 @@ static int launch_nbx(const GemvArgs& a, int grid, int nb_max, hipStream_t strea
             if constexpr (4 * MP <= fused_max_blocks(MP) && D <= 4) return launch_one<MP, RT, D, 4>(a, grid, stream);
         } else if (nb_max <= 8) {
             if constexpr (8 * MP <= fused_max_blocks(MP) && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 8>(a, grid, stream);
-        } else {
+        } else if (nb_max <= 16) {
             if constexpr (16 * MP <= fused_max_blocks(MP) && D == max_depth<MP, kFused>(RT)) return launch_one<MP, RT, D, 16>(a, grid, stream);
         }
-        return -6;
+        return -6;  // no instantiation holds this many blocks per wavefront: gemv_can_fuse() excludes it
     }
 }
 
@@ -533,7 +533,7 @@ bool gemv_can_fuse(int64_t M, int64_t K) {
     int mp = 1;
     while (mp < M) mp <<= 1;
     const int64_t nb_max = (K / kBlock + kGemvWaves - 1) / kGemvWaves;
-    return mp <= 8 && nb_max * mp <= fused_max_blocks(mp);
+    return mp <= 8 && nb_max <= 16 && nb_max * mp <= fused_max_blocks(mp);  // 16: the largest NBX
 }
 
 int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
