@@ -34,6 +34,7 @@
 
 #include "itq3s_dev.h"
 #include <atomic>
+#include <type_traits>
 
 #include "itq3s_kernels.h"
 
@@ -272,12 +273,14 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
 
     // loads of step j (block wave + j*W against all row tiles of the workgroup); past the end of
     // the list, and for missing row tiles, tile 0 / block 0 stand in (never used)
-    auto issue = [&](Slot& s, int j) {
+    // Tiles [R0, R1) of step j.  The activations of the step (direct path) travel with the first part.
+    auto issue_part = [&](Slot& s, int j, auto r0c, auto r1c) {
+        constexpr int R0 = decltype(r0c)::value, R1 = decltype(r1c)::value;
         const bool live = j < nb;
         const int b = wave + j * W;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) load_tile(s.t[rt], slot_codes[rt], slot_scales[rt], live ? b : 0, lane);
-        if constexpr (!kFused) {
+        for (int rt = R0; rt < R1; ++rt) load_tile(s.t[rt], slot_codes[rt], slot_scales[rt], live ? b : 0, lane);
+        if constexpr (!kFused && R0 == 0) {
             const int bb = live ? b : 0;
 #pragma unroll
             for (int t = 0; t < 8; ++t) s.xf[t] = *reinterpret_cast<const half8*>(a.X + ((size_t)((bb * 8 + t) * 4 + g) * MP + mm) * 8);
@@ -294,45 +297,76 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
             }
         }
     };
+    auto issue = [&](Slot& s, int j) { issue_part(s, j, std::integral_constant<int, 0>{}, std::integral_constant<int, RT>{}); };
 
-    auto compute = [&](const Slot& s, int j) {
+    struct StepOperands {
         half8 Xf[8];
         floatx4 sv, ev;
+    };
+    auto prepare = [&](StepOperands& o, const Slot& s, int j) {
         if constexpr (kFused) {
             const _Float16* xb = xs + (size_t)j * MP * 256;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) Xf[t] = *reinterpret_cast<const half8*>(xb + ((t * 4 + g) * MP + mm) * 8);
+            for (int t = 0; t < 8; ++t) o.Xf[t] = *reinterpret_cast<const half8*>(xb + ((t * 4 + g) * MP + mm) * 8);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                if constexpr (!kMfmaSum) sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
-                ev[i] = se[j * MP + ((4 * g + i) & (MP - 1))];
+                if constexpr (!kMfmaSum) o.sv[i] = ss[j * MP + ((4 * g + i) & (MP - 1))];
+                o.ev[i] = se[j * MP + ((4 * g + i) & (MP - 1))];
             }
         } else {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) Xf[t] = s.xf[t];
-            sv = s.sv;
-            ev = s.ev;
+            for (int t = 0; t < 8; ++t) o.Xf[t] = s.xf[t];
+            o.sv = s.sv;
+            o.ev = s.ev;
         }
         if constexpr (kFused && kMfmaSum) {
             floatx4 sacc = {0.f, 0.f, 0.f, 0.f};
             const half8 ones = as_half8(0x04000400u, 0x04000400u, 0x04000400u, 0x04000400u);  // 2^-14 each
 #pragma unroll
-            for (int t = 0; t < 8; ++t) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf[t], ones, sacc, 0, 0, 0);
+            for (int t = 0; t < 8; ++t) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(o.Xf[t], ones, sacc, 0, 0, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sv[i] = sacc[i] * 16384.0f;
+            for (int i = 0; i < 4; ++i) o.sv[i] = sacc[i] * 16384.0f;
         }
+    };
+    auto compute_part = [&](const StepOperands& o, const Slot& s, auto r0c, auto r1c) {
+        constexpr int R0 = decltype(r0c)::value, R1 = decltype(r1c)::value;
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
+        for (int rt = R0; rt < R1; ++rt) {
             if (rt < cnt) {
                 const TileRegs& tr = s.t[rt];
-                const floatx4 c = tile_dot(tr.lo, Xf);
+                const floatx4 c = tile_dot(tr.lo, o.Xf);
                 bad |= tr.hi.x | tr.hi.y;
                 const float d = f16_bits_to_f32(tr.sc & 0xffffu);
                 const float z = f16_bits_to_f32(tr.sc >> 16);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    acc[rt][i] = __builtin_fmaf(d, __builtin_fmaf(c[i], 16384.0f, -__builtin_fmaf(z, ev[i], sv[i])), acc[rt][i]);
+                    acc[rt][i] = __builtin_fmaf(d, __builtin_fmaf(c[i], 16384.0f, -__builtin_fmaf(z, o.ev[i], o.sv[i])), acc[rt][i]);
             }
+        }
+    };
+    auto compute = [&](const Slot& s, int j) {
+        StepOperands o;
+        prepare(o, s, j);
+        compute_part(o, s, std::integral_constant<int, 0>{}, std::integral_constant<int, RT>{});
+    };
+    // One step of the pipeline: loads of step jn into `in`, arithmetic of step j from `cur`.  With many row
+    // tiles the step runs in two halves (loads of the first tiles, arithmetic of the first tiles, then the
+    // rest), so that the registers of the tiles already consumed carry the second half of the loads: the
+    // two ring slots are never live in full at the same time.
+    constexpr bool kHalves = RT >= 5;
+    constexpr int RH = kHalves ? (RT + 1) / 2 : RT;
+    auto step = [&](Slot& in, int jn, const Slot& cur, int j) {
+        if constexpr (!kHalves) {
+            issue(in, jn);
+            compute(cur, j);
+        } else {
+            StepOperands o;
+            issue_part(in, jn, std::integral_constant<int, 0>{}, std::integral_constant<int, RH>{});
+            prepare(o, cur, j);
+            compute_part(o, cur, std::integral_constant<int, 0>{}, std::integral_constant<int, RH>{});
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(in, jn, std::integral_constant<int, RH>{}, std::integral_constant<int, RT>{});
+            compute_part(o, cur, std::integral_constant<int, RH>{}, std::integral_constant<int, RT>{});
         }
     };
 
@@ -393,8 +427,8 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         // no stand-in loads behind the last step.
 #pragma unroll
         for (int j = 0; j < NBX; ++j) {
-            if (j + D < NBX) issue(ring[(j + D) % NB], j + D);
-            compute(ring[j % NB], j);
+            if (j + D < NBX) step(ring[(j + D) % NB], j + D, ring[j % NB], j);
+            else compute(ring[j % NB], j);
         }
     } else {
         // ---- steady state: NB steps per trip, every prefetch is a live step
@@ -402,16 +436,14 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
         for (; bi + NB + D <= nb; bi += NB) {
 #pragma unroll
             for (int k = 0; k < NB; ++k) {
-                issue(ring[(k + D) % NB], bi + k + D);
-                compute(ring[k], bi + k);
+                step(ring[(k + D) % NB], bi + k + D, ring[k], bi + k);
             }
         }
         // ---- tail: fewer than NB + D steps left
 #pragma unroll
         for (int k = 0; k < NB + D - 1; ++k) {
             if (bi + k >= nb) break;  // straight line up to the exit: no merge point between steps
-            issue(ring[(k + D) % NB], bi + k + D);
-            compute(ring[k % NB], bi + k);
+            step(ring[(k + D) % NB], bi + k + D, ring[k % NB], bi + k);
         }
     }
 
@@ -478,7 +510,7 @@ static int cu_count() {
 template <int MP, bool kFused>
 constexpr int max_depth(int rt) {
     if (kFused) return rt <= 2 ? 4 : (rt == 3 || (rt == 4 && MP <= 2)) ? 2 : 1;
-    return rt == 1 ? 4 : rt <= 3 ? 2 : 1;
+    return rt == 1 ? (MP >= 8 ? 2 : 4) : rt <= 3 ? 2 : 1;  // (8 rows and more, depth 4: the ring would spill)
 }
 
 // Smallest of 2, 4, 8, 16 that holds nb_max blocks per wavefront (fused path); 0 = direct.
