@@ -430,6 +430,58 @@ def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
             assert torch.equal(a, b)
 
 
+def test_calls_captured_in_a_graph_replay_like_eager(gpu, ref):
+    """Every entry point, on every path of the matmul (in-kernel rotation, rotation launch, two passes,
+    tiled with and without split-K, grouped), captured once into a HIP graph; between replays the outputs
+    and the workspace are overwritten with garbage and eager work runs; every replay must reproduce the
+    eager results bit for bit (nothing may depend on state a previous replay left behind)."""
+    torch, binding = gpu
+    K = 2048
+    cases = [(1, 272, K), (16, 100, 36864), (20, 300, K), (200, 300, K), (300, 2100, 512)]
+    packed, xs = [], []
+    for i, (M, N, Kc) in enumerate(cases):
+        c, s = synth.random_packed(N, Kc, "graph", i, z_fraction=0.02)
+        packed.append((to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32))))
+        xs.append(to_dev(torch, synth.activations(M, Kc, "graph", i)))
+    group = [(packed[0][0], packed[0][1], 272), (packed[2][0], packed[2][1], 300)]
+    Wq = to_dev(torch, synth.weights(64, 512, "graph"))
+    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, Kc) for M, N, Kc in cases), dtype=torch.uint8, device="cuda")
+    outs = [torch.empty((M, N), dtype=torch.float32, device="cuda") for M, N, Kc in cases]
+    gouts = [torch.empty((3, n), dtype=torch.float16, device="cuda") for n in (272, 300)]
+    qc = torch.empty(binding.itq3s_codes_bytes(64, 512) // 4, dtype=torch.int32, device="cuda")
+    qs = torch.empty(binding.itq3s_scales_bytes(64, 512) // 4, dtype=torch.int32, device="cuda")
+    deq = torch.empty((272, K), dtype=torch.float32, device="cuda")
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def enqueue():
+        for (M, N, Kc), p, x, o in zip(cases, packed, xs, outs):
+            binding.itq3s_matmul(*p, N, Kc, x, out=o, workspace=ws, status_flags=flags)
+        binding.itq3s_matmul_grouped(group, K, xs[2][:3], outs=gouts, workspace=ws)
+        binding.itq3s_quantize(Wq, codes=qc, scales=qs, status_flags=flags)
+        binding.itq3s_dequantize(*packed[0], 272, K, out=deq, status_flags=flags)
+
+    results = lambda: [t.clone() for t in outs + gouts + [qc, qs, deq, flags]]
+    enqueue()
+    torch.cuda.synchronize()
+    eager = results()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enqueue()
+    for rep in range(3):
+        for t in outs + gouts + [deq]:
+            t.fill_(float("nan"))
+        qc.fill_(-1)
+        qs.fill_(-1)
+        ws.fill_(0xA5 + rep)
+        torch.cuda.synchronize()
+        g.replay()
+        # eager work of the program between the replays
+        binding.itq3s_matmul(*packed[0], 272, K, xs[0])
+        torch.cuda.synchronize()
+        for a, b in zip(eager, results()):
+            assert torch.equal(a, b), rep
+
+
 def test_matmul_from_two_host_threads(gpu, ref):
     """Two host threads call the library at the same time, each with its own workspace and outputs
     (streaming, two-pass and tiled shapes, one thread through the timed entry point): every result
