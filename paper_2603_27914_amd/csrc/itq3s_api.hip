@@ -58,7 +58,7 @@ int itq3s_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* 
                    void* stream) {
     if (!W || !codes || !scales) return ITQ3S_ERR_NULL;
     if (N <= 0 || K <= 0 || K % 256 != 0 || ldw < K) return ITQ3S_ERR_SHAPE;
-    if (((N + 15) / 16) * (K / 256) > 0x7fffffffLL) return ITQ3S_ERR_SHAPE;
+    if (((N + 15) / 16) * (K / 256) > 0x3fffffffLL) return ITQ3S_ERR_SHAPE;  // two workgroups per tile, 32-bit grid
     if (!aligned(W, 16) || ldw % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
     return itq3s::launch_quantize(W, N, K, ldw, codes, scales, status_flags, static_cast<hipStream_t>(stream));
