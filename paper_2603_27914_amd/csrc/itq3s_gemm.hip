@@ -44,16 +44,36 @@ struct GemmArgs {
     int splits;
 };
 
-// Zero-point term of a wavefront's output block that has already been stored: columns
-// n_first .. n_first + 63, rows m_first .. m_first + MROWS - 1.  Lane l walks the scale words of
-// column n_first + l, sixteen blocks per batch (independent loads).  For each block with z != 0 -- a
-// fraction of a percent on real weights -- the whole wavefront subtracts d z 16 x[m][256 b] from that
-// column, one row per lane.  Per output element the blocks are applied in ascending order by one lane
-// at a time, so the result does not depend on scheduling.  Working on memory keeps the rare path
-// out of the register budget of the main loop.
-template <int MROWS>
-__device__ __forceinline__ void subtract_zero_points_wave(const GemmArgs& a, int64_t n_first, int64_t m_first, int lane) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's own stores of the block have completed
+// LDS accesses by raw byte address, hidden from the compiler like every other LDS read of this file
+// (it would order visible LDS accesses after all outstanding global -> LDS copies).
+__device__ __forceinline__ void lds_write_b32(uint32_t addr, uint32_t v) { asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory"); }
+__device__ __forceinline__ void lds_add_f32(uint32_t addr, float v) { asm volatile("ds_add_f32 %0, %1" ::"v"(addr), "v"(v) : "memory"); }
+__device__ __forceinline__ uint32_t lds_read_f32_bits_now(uint32_t addr) {
+    uint32_t r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(addr) : "memory");
+    return r;
+}
+__device__ __forceinline__ float lds_read_f32_now(uint32_t addr) {
+    float r;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(addr) : "memory");
+    return r;
+}
+
+// Zero-point terms of a wavefront's output block, columns n_first .. n_first + 63, rows m_first ..
+// m_first + ROWS - 1, summed in fp32 into a wavefront-private LDS table (ROWS x 64 floats at byte
+// address `table`; element (row, col) at word 64 row + (col + row) % 64, which spreads a column over
+// the banks) -- they are subtracted from the accumulators BEFORE the output is rounded: with fp16
+// outputs, correcting the stored value instead would round a sum that still contains the +z offset of
+// every code and lose up to 2^-11 of that larger number.  Lane l walks the scale words of column
+// n_first + l, sixteen blocks per batch (independent loads).  For each block with z != 0 -- a fraction
+// of a percent on real weights -- the whole wavefront adds d z 16 x[m][256 b] to that column of the
+// table, one row per lane.  Per element the blocks are added in ascending order by one lane at a
+// time, so the result does not depend on scheduling.
+template <int ROWS>
+__device__ __forceinline__ void zero_point_terms(const GemmArgs& a, int64_t n_first, int64_t m_first, int lane, uint32_t table) {
+#pragma unroll 8
+    for (int i = 0; i < ROWS; ++i) lds_write_b32(table + (uint32_t)(i * 64 + lane) * 4u, 0u);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     const int64_t n = n_first + lane;
     const int64_t nc = n < a.N ? n : a.N - 1;
     const uint32_t* sc = a.scales + (nc >> 4) * a.KB * kTileRows + (nc & 15);
@@ -71,24 +91,19 @@ __device__ __forceinline__ void subtract_zero_points_wave(const GemmArgs& a, int
                 todo &= todo - 1ull;
                 const uint32_t word = (uint32_t)__builtin_amdgcn_readlane((int)w[u], src);
                 const float dz = f16_bits_to_f32(word & 0xffffu) * f16_bits_to_f32(word >> 16);
-                const int64_t nh = n_first + src;
 #pragma unroll 1
-                for (int r = 0; r < MROWS; r += kWave) {
-                    const int64_t m = m_first + r + lane;
-                    if (m < a.M && r + lane < MROWS) {
+                for (int r = 0; r < ROWS; r += kWave) {
+                    const int row = r + lane;
+                    const int64_t m = m_first + row;
+                    if (m < a.M && row < ROWS) {
                         const float t = dz * (16.0f * (float)a.X[m * a.ldx + (int64_t)(b0 + u) * kBlock]);
-                        if (a.y_f16) {
-                            _Float16* y = reinterpret_cast<_Float16*>(a.Y) + m * a.ldy + nh;
-                            *y = (_Float16)((float)*y - t);
-                        } else {
-                            float* y = reinterpret_cast<float*>(a.Y) + m * a.ldy + nh;
-                            *y = *y - t;
-                        }
+                        lds_add_f32(table + (uint32_t)(row * 64 + ((src + row) & 63)) * 4u, t);
                     }
                 }
             }
         }
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -142,7 +157,8 @@ constexpr int kWRingBase = kXStages * kXStageBytes;         // 49152
 constexpr int kWStageBytes = 4 * 1024;                      // 4 wavefronts x 64 lanes x 16 bytes
 constexpr int kSRingBase = kWRingBase + kWStages * kWStageBytes;  // 65536
 constexpr int kSStageBytes = 4 * 256;                       // 4 wavefronts x 64 lanes x 4 bytes
-constexpr int kGemmLds = kSRingBase + kWStages * kSStageBytes;    // 69632
+constexpr int kDoneWord = kSRingBase + kWStages * kSStageBytes;   // 69632: count of wavefronts that are done with the rings
+constexpr int kGemmLds = kDoneWord + 16;
 constexpr int kPanel = 4;                                   // tile rows per panel
 
 template <int OFF>
@@ -176,31 +192,47 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 }
 
 // Store 32 rows (m_first ..) of a wavefront's 64 columns (n0 + 64 wn ..).  Accumulator register v of a
-// 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32.
-__device__ __forceinline__ void store_rows(const GemmArgs& a, const floatx16 (&acc)[2], int64_t m_first, int64_t n0, int wn, int lane) {
+// 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32.  kTerms: minus the zero-point
+// terms of these rows, which start at row `row0` of the wavefront's LDS table (zero_point_terms()).
+template <bool kTerms>
+__device__ __forceinline__ void store_rows(const GemmArgs& a, const floatx16 (&acc)[2], int64_t m_first, int64_t n0, int wn, int lane,
+                                           int row0 = 0, uint32_t table = 0) {
     const int l32 = lane & 31, kg = lane >> 5;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int64_t n = n0 + wn * 64 + j * 32 + l32;
+        floatx16 terms;
+        if constexpr (kTerms) {
+            // sixteen reads in flight, one wait
+            uint32_t t[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + 8 * (v >> 2) + 4 * kg + (v & 3), col = 32 * j + l32;
+                asm volatile("ds_read_b32 %0, %1" : "=v"(t[v]) : "v"(table + (uint32_t)(row * 64 + ((col + row) & 63)) * 4u) : "memory");
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7]), "+v"(t[8]), "+v"(t[9]),
+                           "+v"(t[10]), "+v"(t[11]), "+v"(t[12]), "+v"(t[13]), "+v"(t[14]), "+v"(t[15]));
+#pragma unroll
+            for (int v = 0; v < 16; ++v) terms[v] = __builtin_bit_cast(float, t[v]);
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int64_t m = m_first + 8 * (v >> 2) + 4 * kg + (v & 3);
             if (m < a.M && n < a.N) {
-                if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[j][v];
-                else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[j][v];
+                float y = acc[j][v];
+                if constexpr (kTerms) y = y - terms[v];
+                if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)y;
+                else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = y;
             }
         }
     }
 }
 
-// Store a wavefront's 128 x 64 block (rows m0.., columns n0 + 64 wn ..) and apply the zero-point term
-// if one was met (columns past N read clamped rows and may trigger it needlessly; nothing is stored
-// for them).
-__device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&acc)[4][2], int64_t m0, int64_t n0, int wn, int lane,
-                                           bool zero_points) {
+// Store a wavefront's 128 x 64 block (rows m0.., columns n0 + 64 wn ..).
+__device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&acc)[4][2], int64_t m0, int64_t n0, int wn, int lane) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) store_rows(a, acc[i], m0 + i * 32, n0, wn, lane);
-    if (zero_points) subtract_zero_points_wave<128>(a, n0 + wn * 64, m0, lane);
+    for (int i = 0; i < 4; ++i) store_rows<false>(a, acc[i], m0 + i * 32, n0, wn, lane);
 }
 
 // (two wavefronts per SIMD: at most 256 registers)
@@ -427,6 +459,10 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_waitcnt vmcnt(2)" ::: "memory");  // quarter 1 has landed as well; only the two copies of copy_w(2) may be in flight
+    if (tid == 0) {
+        lds_write_b32(lds_base + kDoneWord, 0u);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
     __builtin_amdgcn_s_barrier();
     // The two register sets of the weights alternate by name, so trips come in pairs: the first trip
     // on its own, pairs (1,2), (3,4), ..., and the last trip (K is a multiple of 256: the number of
@@ -443,6 +479,10 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     // last step of the last quarter (the words it unpacks are never used)
     step(af1, wa0.x, wa1.x);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the look-ahead copies past the last quarter still target this workgroup's LDS
+    // ... and this wavefront reads the rings no more.  Counted rather than met at a barrier: only a
+    // wavefront that needs the rings' space for its zero-point table waits for the other three, and
+    // every wavefront gets here without waiting for anything.
+    if (lane == 0) asm volatile("ds_add_u32 %0, %1" ::"v"(lds_base + kDoneWord), "v"(1u) : "memory");
 
     // Format check, apart from the arithmetic: the high plane of the workgroup's 16 tile rows must be
     // zero (128 words per tile, a quarter of the packed bytes, read once more here).
@@ -471,7 +511,22 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         if (zero_points && lane == 0) atomicOr(a.zflags + t, 1u);
         return;
     }
-    store_tile(a, acc, m0, n0, wn, lane, zero_points);
+    if (zero_points) {
+        // (columns past N read clamped rows and may trigger this needlessly; nothing is stored for them)
+        // the table of this wavefront takes 16 KiB of the rings, once all four wavefronts have drained
+        // their copies and left the main loop (rows in two halves of 64)
+        static_assert(4 * 64 * 64 * 4 <= kGemmLds, "four tables of 64 x 64 floats");
+        const uint32_t table = lds_base + (uint32_t)wave * (64 * 64 * 4);
+        while (__builtin_amdgcn_readfirstlane((int)lds_read_f32_bits_now(lds_base + kDoneWord)) != GT / kWave) __builtin_amdgcn_s_sleep(2);
+        zero_point_terms<64>(a, n0 + wn * 64, m0, lane, table);
+        store_rows<true>(a, acc[0], m0, n0, wn, lane, 0, table);
+        store_rows<true>(a, acc[1], m0 + 32, n0, wn, lane, 32, table);
+        zero_point_terms<64>(a, n0 + wn * 64, m0 + 64, lane, table);
+        store_rows<true>(a, acc[2], m0 + 64, n0, wn, lane, 0, table);
+        store_rows<true>(a, acc[3], m0 + 96, n0, wn, lane, 32, table);
+        return;
+    }
+    store_tile(a, acc, m0, n0, wn, lane);
 }
 
 // Second launch of a split-K matmul: four workgroups per tile, one per 32-row slab, add the shares
@@ -498,8 +553,14 @@ __global__ __launch_bounds__(GT) void gemm_reduce_kernel(const GemmArgs a, int t
             for (int e = 0; e < 4; ++e) acc[j][4 * c + e] = sum[e];
         }
     const int64_t m_first = (int64_t)tm * GM + i * 32, n0 = (int64_t)tn * GN;
-    store_rows(a, acc, m_first, n0, wn, lane);
-    if (a.zflags[t] != 0u) subtract_zero_points_wave<32>(a, n0 + wn * 64, m_first, lane);
+    if (a.zflags[t] != 0u) {
+        __shared__ __align__(16) float tables[4 * 32 * 64];  // one per wavefront
+        const uint32_t table = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)tables + (uint32_t)wn * (32 * 64 * 4);
+        zero_point_terms<32>(a, n0 + wn * 64, m_first, lane, table);
+        store_rows<true>(a, acc, m_first, n0, wn, lane, 0, table);
+        return;
+    }
+    store_rows<false>(a, acc, m_first, n0, wn, lane);
 }
 
 // Splits of K per tile: when the tiles alone leave three quarters of the chip idle, enough workgroups
