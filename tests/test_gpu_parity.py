@@ -430,6 +430,21 @@ def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("M,N,K", [(129, 100, 8192), (200, 300, 4096), (40, 100, 8192), (8, 100, 8192)])
+def test_matmul_fp16_output_with_zero_points_in_most_blocks(gpu, ref, M, N, K):
+    """Rows whose blocks nearly all carry a zero-point (a constant offset in the weights), fp16 output: the
+    zero-point terms must be applied before the output is rounded -- subtracting them from an already
+    rounded fp16 value costs up to 2^-11 of the much larger uncorrected sum (3e-3 of a row was seen)."""
+    torch, binding = gpu
+    codes, scales = synth.random_packed(N, K, "zp16", M, z_fraction=0.9)
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    X = synth.activations(M, K, "zp16", N)
+    want = ref.matmul(codes, scales, N, K, X)
+    for dtype in (torch.float16, torch.float32):
+        got = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), dtype=dtype).cpu().numpy()
+        assert rel_rows(got, want) <= (1e-3 if dtype == torch.float16 else 6e-4)
+
+
 def test_calls_captured_in_a_graph_replay_like_eager(gpu, ref):
     """Every entry point, on every path of the matmul (in-kernel rotation, rotation launch, two passes,
     tiled with and without split-K, grouped), captured once into a HIP graph; between replays the outputs
