@@ -106,6 +106,70 @@ __device__ __forceinline__ void zero_point_terms(const GemmArgs& a, int64_t n_fi
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
+// The common case of the above -- the zero-points of a wavefront's 64 columns sit in at most eight of
+// them -- needs no table of all columns: one 128-row strip of floats per such column (strip_offset())
+// fits the wavefront's own corner of the weight ring (1 KiB of each of its four stages: two strips
+// each), so nothing is shared, nobody is waited for, and one scan serves all 128 rows.  cols receives
+// the columns (0..63, -1: slot unused).  Returns false, with the strips in an undefined state, if a
+// ninth column turns up.
+constexpr int kStrips = 8;
+struct StripColumns {
+    int c[kStrips];
+};
+__device__ __forceinline__ uint32_t strip_offset(int slot) { return (uint32_t)((slot >> 1) * 4096 + (slot & 1) * 512); }
+__device__ __forceinline__ bool zero_point_terms_few_columns(const GemmArgs& a, int64_t n_first, int64_t m_first, int lane, uint32_t strips,
+                                                             StripColumns& cols) {
+#pragma unroll
+    for (int s = 0; s < kStrips; ++s) {
+        cols.c[s] = -1;
+        lds_write_b32(strips + strip_offset(s) + (uint32_t)(4 * lane), 0u);
+        lds_write_b32(strips + strip_offset(s) + (uint32_t)(4 * (lane + 64)), 0u);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const int64_t n = n_first + lane;
+    const int64_t nc = n < a.N ? n : a.N - 1;
+    const uint32_t* sc = a.scales + (nc >> 4) * a.KB * kTileRows + (nc & 15);
+#pragma unroll 1
+    for (int b0 = 0; b0 < a.KB; b0 += 16) {
+        uint32_t w[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) w[u] = sc[(int64_t)(b0 + u < a.KB ? b0 + u : a.KB - 1) * kTileRows];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const bool hit = (w[u] & 0x7fff0000u) != 0u && n < a.N && b0 + u < a.KB;
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(hit);
+            while (todo != 0ull) {  // uniform
+                const int src = __builtin_ctzll(todo);
+                todo &= todo - 1ull;
+                // the column's slot, or the first free one (uniform; static indices only)
+                int slot = -1;
+#pragma unroll
+                for (int q = kStrips - 1; q >= 0; --q) slot = cols.c[q] == src ? q : slot;
+                if (slot < 0) {
+#pragma unroll
+                    for (int q = kStrips - 1; q >= 0; --q) slot = cols.c[q] < 0 ? q : slot;
+                    if (slot < 0) return false;
+#pragma unroll
+                    for (int q = 0; q < kStrips; ++q) cols.c[q] = q == slot ? src : cols.c[q];
+                }
+                const uint32_t word = (uint32_t)__builtin_amdgcn_readlane((int)w[u], src);
+                const float dz = f16_bits_to_f32(word & 0xffffu) * f16_bits_to_f32(word >> 16);
+#pragma unroll
+                for (int r = 0; r < 128; r += kWave) {
+                    const int row = r + lane;
+                    const int64_t m = m_first + row;
+                    if (m < a.M) {
+                        const float t = dz * (16.0f * (float)a.X[m * a.ldx + (int64_t)(b0 + u) * kBlock]);
+                        lds_add_f32(strips + strip_offset(slot) + (uint32_t)(4 * row), t);
+                    }
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    return true;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Workgroup tile 128 (m) x 256 (n), four wavefronts side by side along n, wavefront tile 128 x 64 =
 // 4 x 2 v_mfma_f32_32x32x16_f16 (128 accumulator registers per lane), K in quarters of a block
@@ -194,34 +258,42 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 // Store 32 rows (m_first ..) of a wavefront's 64 columns (n0 + 64 wn ..).  Accumulator register v of a
 // 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32.  kTerms: minus the zero-point
 // terms of these rows, which start at row `row0` of the wavefront's LDS table (zero_point_terms()).
-template <bool kTerms>
+template <int kTerms>  // 0: none; 1: table of all columns (row0: its row of m_first); 2: strips of a few columns (row0 likewise)
 __device__ __forceinline__ void store_rows(const GemmArgs& a, const floatx16 (&acc)[2], int64_t m_first, int64_t n0, int wn, int lane,
-                                           int row0 = 0, uint32_t table = 0) {
+                                           int row0 = 0, uint32_t table = 0, const StripColumns* cols = nullptr) {
     const int l32 = lane & 31, kg = lane >> 5;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int64_t n = n0 + wn * 64 + j * 32 + l32;
         floatx16 terms;
-        if constexpr (kTerms) {
+        if constexpr (kTerms != 0) {
+            const int col = 32 * j + l32;
+            int slot = -1;  // (strips only)
+            if constexpr (kTerms == 2) {
+#pragma unroll
+                for (int q = 0; q < kStrips; ++q) slot = cols->c[q] == col ? q : slot;
+            }
             // sixteen reads in flight, one wait
             uint32_t t[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = row0 + 8 * (v >> 2) + 4 * kg + (v & 3), col = 32 * j + l32;
-                asm volatile("ds_read_b32 %0, %1" : "=v"(t[v]) : "v"(table + (uint32_t)(row * 64 + ((col + row) & 63)) * 4u) : "memory");
+                const int row = row0 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const uint32_t addr = kTerms == 1 ? table + (uint32_t)(row * 64 + ((col + row) & 63)) * 4u
+                                                  : table + strip_offset(slot < 0 ? 0 : slot) + (uint32_t)(4 * row);
+                asm volatile("ds_read_b32 %0, %1" : "=v"(t[v]) : "v"(addr) : "memory");
             }
             asm volatile("s_waitcnt lgkmcnt(0)"
                          : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7]), "+v"(t[8]), "+v"(t[9]),
                            "+v"(t[10]), "+v"(t[11]), "+v"(t[12]), "+v"(t[13]), "+v"(t[14]), "+v"(t[15]));
 #pragma unroll
-            for (int v = 0; v < 16; ++v) terms[v] = __builtin_bit_cast(float, t[v]);
+            for (int v = 0; v < 16; ++v) terms[v] = (kTerms == 2 && slot < 0) ? 0.0f : __builtin_bit_cast(float, t[v]);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int64_t m = m_first + 8 * (v >> 2) + 4 * kg + (v & 3);
             if (m < a.M && n < a.N) {
                 float y = acc[j][v];
-                if constexpr (kTerms) y = y - terms[v];
+                if constexpr (kTerms != 0) y = y - terms[v];
                 if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)y;
                 else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = y;
             }
@@ -232,7 +304,7 @@ __device__ __forceinline__ void store_rows(const GemmArgs& a, const floatx16 (&a
 // Store a wavefront's 128 x 64 block (rows m0.., columns n0 + 64 wn ..).
 __device__ __forceinline__ void store_tile(const GemmArgs& a, const floatx16 (&acc)[4][2], int64_t m0, int64_t n0, int wn, int lane) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) store_rows<false>(a, acc[i], m0 + i * 32, n0, wn, lane);
+    for (int i = 0; i < 4; ++i) store_rows<0>(a, acc[i], m0 + i * 32, n0, wn, lane);
 }
 
 // (two wavefronts per SIMD: at most 256 registers)
@@ -513,17 +585,29 @@ __global__ __launch_bounds__(GT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
     if (zero_points) {
         // (columns past N read clamped rows and may trigger this needlessly; nothing is stored for them)
-        // the table of this wavefront takes 16 KiB of the rings, once all four wavefronts have drained
-        // their copies and left the main loop (rows in two halves of 64)
-        static_assert(4 * 64 * 64 * 4 <= kGemmLds, "four tables of 64 x 64 floats");
-        const uint32_t table = lds_base + (uint32_t)wave * (64 * 64 * 4);
+        {
+            // first the cheap way: at most eight columns with zero-points, strips in this wavefront's own
+            // corner of the weight ring (its copies have landed; nobody else touches it)
+            const uint32_t strips = lds_base + kWRingBase + (uint32_t)wave * 1024u;
+            StripColumns cols;
+            if (zero_point_terms_few_columns(a, n0 + wn * 64, m0, lane, strips, cols)) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) store_rows<2>(a, acc[i], m0 + 32 * i, n0, wn, lane, 32 * i, strips, &cols);
+                return;
+            }
+        }
+        // otherwise a table of all 64 columns, 32 rows at a time, in the activation ring (which does not
+        // overlap any wavefront's strips) -- once all four wavefronts have drained their copies and left
+        // the main loop
+        static_assert(kWStageBytes == 4096 && kWStages * 2 >= kStrips, "two strips of 128 floats in the wavefront's KiB of every stage");
+        static_assert(4 * 32 * 64 * 4 <= kWRingBase, "four tables of 32 x 64 floats inside the activation ring");
+        const uint32_t table = lds_base + (uint32_t)wave * (32 * 64 * 4);
         while (__builtin_amdgcn_readfirstlane((int)lds_read_f32_bits_now(lds_base + kDoneWord)) != GT / kWave) __builtin_amdgcn_s_sleep(2);
-        zero_point_terms<64>(a, n0 + wn * 64, m0, lane, table);
-        store_rows<true>(a, acc[0], m0, n0, wn, lane, 0, table);
-        store_rows<true>(a, acc[1], m0 + 32, n0, wn, lane, 32, table);
-        zero_point_terms<64>(a, n0 + wn * 64, m0 + 64, lane, table);
-        store_rows<true>(a, acc[2], m0 + 64, n0, wn, lane, 0, table);
-        store_rows<true>(a, acc[3], m0 + 96, n0, wn, lane, 32, table);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            zero_point_terms<32>(a, n0 + wn * 64, m0 + 32 * i, lane, table);
+            store_rows<1>(a, acc[i], m0 + 32 * i, n0, wn, lane, 0, table);
+        }
         return;
     }
     store_tile(a, acc, m0, n0, wn, lane);
@@ -557,10 +641,10 @@ __global__ __launch_bounds__(GT) void gemm_reduce_kernel(const GemmArgs a, int t
         __shared__ __align__(16) float tables[4 * 32 * 64];  // one per wavefront
         const uint32_t table = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)tables + (uint32_t)wn * (32 * 64 * 4);
         zero_point_terms<32>(a, n0 + wn * 64, m_first, lane, table);
-        store_rows<true>(a, acc, m_first, n0, wn, lane, 0, table);
+        store_rows<1>(a, acc, m_first, n0, wn, lane, 0, table);
         return;
     }
-    store_rows<false>(a, acc, m_first, n0, wn, lane);
+    store_rows<0>(a, acc, m_first, n0, wn, lane);
 }
 
 // Splits of K per tile: when the tiles alone leave three quarters of the chip idle, enough workgroups
