@@ -38,10 +38,10 @@ MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 # rocprofv3 --pmc passes over this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
 # counter shows for copy_leg's 1 GiB copy; the summaries and the commands are under profiles/.
 MEASURED_TRAFFIC = {
-    # per launch of the grouped step: fetched (19417.7 + 6570.9 + 34899.0 + 17592.8) / 4 KiB, written
+    # per launch of the grouped step: fetched (19417.6 + 6570.9 + 34898.1 + 17594.1) / 4 KiB, written
     # (48 + 16 + 86 + 16) / 4 KiB, against 19,823,488 algorithmic bytes: 1.6 % of re-reads (the
     # activations, read by every workgroup, and stand-in loads)
-    "llama7b_decode": {"bytes_per_launch": 20133478, "fetch_bytes": 20090982, "write_bytes": 42496,
+    "llama7b_decode": {"bytes_per_launch": 20133555, "fetch_bytes": 20091059, "write_bytes": 42496,
                        "source": "profiles/gemv_quantize_llama7b_decode.hbm_traffic.txt"},
 }
 
