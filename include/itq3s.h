@@ -95,7 +95,8 @@ int itq3s_dequantize(const uint32_t *codes, const uint32_t *scales, int64_t N, i
 /* Fused matmul (problem statement of Alg. 2; Sec. 5.4 for M = 1):  Y[m][n] = sum_k X[m][k] w_hat[n][k].
  * No dequantized weight is written to memory.  M <= 16 takes the bandwidth-bound streaming path
  * (M <= 32: two passes of it), larger M the tiled MFMA path (which accepts K <= 4194304 only:
- * ITQ3S_ERR_SHAPE beyond); fp32 accumulation in both.
+ * ITQ3S_ERR_SHAPE beyond); fp32 accumulation in both, the zero-point terms included: an output
+ * element is rounded once.
  *   X  [in]  device, M x K fp16 row-major, row stride ldx elements (ldx >= K, ldx % 8 == 0,
  *            pointer 16-byte aligned)
  *   Y  [out] device, M x N of y_dtype, row stride ldy elements (ldy >= N); overwritten
