@@ -10,7 +10,8 @@
 // 16 times the chunk's first element: the term is formed from the activations themselves in fp32.
 // Folding z into the fp16 operand instead would multiply the rounding errors of x~ by z.  The term
 // is rare (a fraction of a percent of the blocks on real weights), so the kernel notes while it runs
-// whether a zero-point came by and only then walks the scale words of its columns at the end.
+// whether a zero-point came by and only then walks the scale words of its columns at the end; the
+// terms are subtracted from the accumulators, so an output element is rounded once.
 //
 // k' is the channel order the unpack produces (within each group of 16 channels: 0,8,1,9,...,7,15);
 // the rotation kernel writes x~ in the same order.  A operand = x~ rows, B operand = weight rows, so
