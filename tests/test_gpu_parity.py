@@ -103,6 +103,30 @@ def test_quantize_adversarial_blocks(gpu, ref):
     check_quantize(torch, binding, ref, W3)
 
 
+def test_quantize_blocks_across_the_whole_fp32_range(gpu, ref):
+    """Blocks at every magnitude an fp32 can hold (subnormal to the largest finite numbers), and blocks
+    whose elements span ten decades: the kernel applies the transform's power-of-two factor to the
+    block's scalars instead of its elements, which is bit-identical only as long as no intermediate
+    value leaves the fp64 range -- checked here against the oracle, which scales the elements."""
+    torch, binding = gpu
+    rng = np.random.default_rng(7)
+    rows = []
+    with np.errstate(over="ignore", under="ignore"):
+        for e in range(-45, 39):
+            for _ in range(24):
+                rows.append((rng.standard_normal(256) * 10.0**e).astype(np.float32))
+            for _ in range(8):
+                rows.append((rng.standard_normal(256) * 10.0 ** (e + rng.uniform(-5, 5, size=256))).astype(np.float32))
+    W = np.nan_to_num(np.stack(rows), nan=0.0, posinf=np.finfo(np.float32).max, neginf=-np.finfo(np.float32).max)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    codes, scales = binding.itq3s_quantize(to_dev(torch, W), status_flags=flags)
+    torch.cuda.synchronize()
+    rc, rs, rflags = ref.quantize(W)
+    assert np.array_equal(u32(scales), rs), "scale words differ"
+    assert np.array_equal(u32(codes), rc), "packed codes differ"
+    assert int(flags.item()) == rflags
+
+
 def test_quantize_many_random_blocks(gpu, ref):
     """Half a million heavy-tailed blocks: any disagreement in rounding (sqrt, division, the two
     conversion steps of the scale, the summation order) would flip a scale bit or a code somewhere."""
