@@ -448,8 +448,8 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gemv_kernel(const GemvArgs a)
     }
 
     // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]; slot_out says where
-    // the 16 outputs of a slot go
-    __syncthreads();
+    // the 16 outputs of a slot go.  (red overlaps nothing a wavefront still reads -- the rotated
+    // activations and their sums lie in front of it -- so one barrier, behind the writes, is enough)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
