@@ -11,8 +11,9 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "itq3s_ref.c")
-_LIB = os.path.join(_HERE, "libitq3s_ref.so")
+# (the mutation test of the pins points these at a deliberately broken copy of the source)
+_SRC = os.environ.get("ITQ3S_REF_SRC", os.path.join(_HERE, "itq3s_ref.c"))
+_LIB = os.environ.get("ITQ3S_REF_LIB", os.path.join(_HERE, "libitq3s_ref.so"))
 
 FLAG_NONFINITE, FLAG_SCALE_SAT, FLAG_Z_CLAMP, FLAG_BAD_CODE = 1, 2, 4, 8
 

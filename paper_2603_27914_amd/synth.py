@@ -1,7 +1,7 @@
 """Seeded synthetic inputs with the shapes and value distributions of the benchmark configurations.
 
 This module holds no arithmetic of the method itself (no transform, no coding, no packing): it
-only draws random tensors.  Both the HIP path and the CPU oracle are fed from the bytes produced
+only draws random weight and activation tensors.  Both the HIP path and the CPU oracle are fed from the bytes produced
 here, so that bit-exact comparisons never depend on two random generators agreeing.
 
 Stand-in for real LLM checkpoints (none are available offline): weights are heavy-tailed
@@ -85,24 +85,3 @@ def activations(M, K, *key, outlier_frac=0.005):
         cols = g.choice(K, size=n_out, replace=False)
         X[:, cols] *= np.float32(10.0)
     return X.astype(np.float16)
-
-
-def random_packed(N, K, *key, z_fraction=0.001):
-    """Random but VALID packed tensor (codes uniform in {0,1,2}, fp16 scales near 0.016, a few
-    blocks with a non-zero integer zero-point), for matmul/dequantize tests at sizes where running
-    a quantizer first is too slow.  Returns (codes uint32, scales uint32) in the tiled layout:
-    16-row tiles of 384 words; low plane = 2 bits per code, high plane all zero."""
-    g = _rng("P", N, K, *key)
-    NT, KB = (N + 15) // 16, K // 256
-    c = g.integers(0, 3, size=(NT * KB, 256, 16), dtype=np.uint32)  # [tile][lo word][slot]
-    lo = np.zeros((NT * KB, 256), dtype=np.uint32)
-    for s in range(16):
-        lo |= c[:, :, s] << np.uint32(2 * s)
-    codes = np.zeros((NT * KB, 384), dtype=np.uint32)
-    codes[:, :256] = lo
-    d = (0.016 * np.exp(0.25 * g.standard_normal(size=NT * KB * 16))).astype(np.float16)
-    z = np.zeros(NT * KB * 16, dtype=np.float16)
-    nz = g.random(NT * KB * 16) < z_fraction
-    z[nz] = g.integers(-3, 4, size=int(nz.sum())).astype(np.float16)
-    scales = d.view(np.uint16).astype(np.uint32) | (z.view(np.uint16).astype(np.uint32) << np.uint32(16))
-    return codes.reshape(-1), scales

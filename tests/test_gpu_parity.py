@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 from paper_2603_27914_amd import synth
+from tests.packed_inputs import random_packed, unpack_numpy
 
 pytestmark = pytest.mark.gpu
 
@@ -157,7 +158,7 @@ def test_dequantize_fp32(gpu, ref, N, K):
 def test_dequantize_fp16_and_strided(gpu, ref):
     torch, binding = gpu
     N, K = 100, 512
-    codes, scales = synth.random_packed(N, K, "deq16", z_fraction=0.05)
+    codes, scales = random_packed(N, K, "deq16", z_fraction=0.05)
     want = ref.dequantize(codes, scales, N, K)
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     buf = torch.zeros((N, K + 8), dtype=torch.float16, device="cuda")
@@ -173,7 +174,7 @@ def test_dequantize_fp16_and_strided(gpu, ref):
 
 def test_dequantize_flags_bad_codes(gpu, ref):
     torch, binding = gpu
-    codes, scales = synth.random_packed(32, 512, "bad")
+    codes, scales = random_packed(32, 512, "bad")
     for word, bit in ((7, 3 << 10), (256 + 40, 1 << 9)):
         bad = codes.copy()
         bad[384 * 2 + word] |= np.uint32(bit)
@@ -212,15 +213,34 @@ def run_matmul(torch, binding, ref, codes, scales, N, K, X, out_dtype=None, rows
     Y = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), dtype=out_dtype or torch.float32, status_flags=flags)
     torch.cuda.synchronize()
     assert int(flags.item()) == 0
+    out_f16 = Y.dtype == torch.float16
     Y = Y.float().cpu().numpy()
     if rows is None:
         want = ref.matmul(codes, scales, N, K, X)
+        check_elements(Y, want, codes, scales, N, K, X, out_f16)
         return rel_rows(Y, want)
     worst = 0.0
     for n0, n1 in rows:
         want = ref.matmul(codes, scales, N, K, X, rows=(n0, n1))[:, n0:n1]
         worst = max(worst, rel_rows(Y[:, n0:n1], want))
     return worst
+
+
+def check_elements(Y, want, codes, scales, N, K, X, out_f16=False):
+    """Bound on every single element, next to the per-row bar: the kernels round the rotated
+    activations once to fp16 (relative 2^-11 each) and multiply them with the exact digits d q, the
+    zero-point term is formed in fp32 from the activations themselves, so
+        |Y[m,n] - want[m,n]| <= 2^-11 sum_k |d q[n,k]| |x~[m,k]| <= 2^-11 ||d q[n,:]|| ||x[m,:]||
+    (Cauchy-Schwarz; ||x~|| = ||x||, the rotation is orthogonal), plus the fp32 accumulation and the
+    rounding of the output.  A single wrong digit or scale in a short row breaks it."""
+    c, d, z = unpack_numpy(np.asarray(codes), np.asarray(scales), N, K)
+    dq = (c - 1).astype(np.float64) * np.repeat(d, 256, axis=1)
+    wn = np.linalg.norm(dq, axis=1)                      # [N]
+    xn = np.linalg.norm(X.astype(np.float64), axis=1)    # [M]
+    bound = 1.5 * 2.0 ** -11 * xn[:, None] * wn[None, :] + 2.0 ** (-11 if out_f16 else -22) * np.abs(want) + 1e-30
+    err = np.abs(Y.astype(np.float64) - want)
+    worst = np.max(err / bound)
+    assert worst <= 1.0, "an element misses its bound by a factor %.2f" % worst
 
 
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16, 17, 25, 32])  # 17..32: two passes of the streaming kernel
@@ -233,7 +253,7 @@ def test_matmul_small_m(gpu, ref, M, N, K):
         codes, scales, _ = ref.quantize(W)
         X = synth.activations(M, K, "mm", outlier_frac=0.0 if M == 1 else 0.005)
     else:
-        codes, scales = synth.random_packed(N, K, "mm", M, z_fraction=0.02)
+        codes, scales = random_packed(N, K, "mm", M, z_fraction=0.02)
         X = synth.activations(M, K, "mm", N)
     assert run_matmul(torch, binding, ref, codes, scales, N, K, X) <= MATMUL_TOL
 
@@ -241,7 +261,7 @@ def test_matmul_small_m(gpu, ref, M, N, K):
 @pytest.mark.parametrize("M,N,K", [(40, 100, 256), (17, 48, 512), (64, 256, 1024), (130, 1000, 768), (200, 144, 2048), (512, 384, 4096), (129, 257, 1280)])
 def test_matmul_tiled_path(gpu, ref, M, N, K):
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "gemm", M, z_fraction=0.02)
+    codes, scales = random_packed(N, K, "gemm", M, z_fraction=0.02)
     X = synth.activations(M, K, "gemm", N)
     assert run_matmul(torch, binding, ref, codes, scales, N, K, X) <= MATMUL_TOL
 
@@ -265,7 +285,7 @@ def test_matmul_quantized_weights_tiled_path(gpu, ref):
 def test_matmul_fp16_output_and_strides(gpu, ref, M):
     torch, binding = gpu
     N, K = 304, 1024
-    codes, scales = synth.random_packed(N, K, "f16out", M)
+    codes, scales = random_packed(N, K, "f16out", M)
     X = synth.activations(M, K, "f16out")
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     xbuf = torch.zeros((M, K + 16), dtype=torch.float16, device="cuda")
@@ -281,7 +301,7 @@ def test_matmul_fp16_output_and_strides(gpu, ref, M):
 def test_matmul_is_deterministic(gpu, ref):
     torch, binding = gpu
     N, K = 4096, 4096
-    codes, scales = synth.random_packed(N, K, "det")
+    codes, scales = random_packed(N, K, "det")
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     for M in (1, 8, 64):
         X = to_dev(torch, synth.activations(M, K, "det"))
@@ -295,7 +315,7 @@ def test_matmul_timed_variant_same_result_and_positive_time(gpu, ref, M, N, K):
     """The measurement entry point runs the same kernels: identical output, a plausible duration,
     and a plain call afterwards is unaffected (the armed events are consumed)."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "timed")
+    codes, scales = random_packed(N, K, "timed")
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     X = to_dev(torch, synth.activations(M, K, "timed"))
     want = binding.itq3s_matmul(cd, sd, N, K, X).cpu().numpy()
@@ -324,7 +344,7 @@ def test_matmul_grouped_matches_oracle_and_single_calls(gpu, ref, K, Ns, Ms):
     """One grouped call = the separate calls, bit for bit (same kernels, same order of sums), and
     within tolerance of the oracle; full rows for the small tensors, sampled rows for the large."""
     torch, binding = gpu
-    packed = [synth.random_packed(N, K, "grp", i) for i, N in enumerate(Ns)]
+    packed = [random_packed(N, K, "grp", i) for i, N in enumerate(Ns)]
     dev = [(to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)), N) for (c, s), N in zip(packed, Ns)]
     rng = np.random.default_rng(5)
     for M in Ms:
@@ -351,7 +371,7 @@ def test_matmul_grouped_matches_oracle_and_single_calls(gpu, ref, K, Ns, Ms):
 def test_matmul_grouped_rejects_bad_arguments(gpu, ref):
     torch, binding = gpu
     K = 512
-    c, s = synth.random_packed(32, K, "grp-bad")
+    c, s = random_packed(32, K, "grp-bad")
     dev = (to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)), 32)
     X = to_dev(torch, synth.activations(1, K, "grp-bad"))
     with pytest.raises(binding.Itq3sError):
@@ -365,11 +385,11 @@ def test_matmul_grouped_rejects_bad_arguments(gpu, ref):
 
 @pytest.mark.parametrize("M", [1, 4, 16, 40, 300])
 def test_matmul_extreme_zero_points(gpu, ref, M):
-    """Zero-points over the whole stored range (+-2048), on every path: the streaming kernel applies
-    z in fp32, the tiled kernels in fp16 (exact up to |z| of about 1000, then within 1/2000)."""
+    """Zero-points over the whole stored range (+-2048), on every path: every kernel forms the
+    zero-point term in fp32 from the activations themselves."""
     torch, binding = gpu
     N, K = 600, 1024
-    codes, scales = synth.random_packed(N, K, "bigz")
+    codes, scales = random_packed(N, K, "bigz")
     rng = np.random.default_rng(11)
     z = np.zeros(scales.size, dtype=np.float16)
     pick = rng.random(scales.size) < 0.05
@@ -387,7 +407,7 @@ def test_matmul_large_tile_kernel_ragged_and_zero_points(gpu, ref, M, N, K):
     """Enough 256 x 256 tiles for the large-M kernel; ragged M and N; zero-points over the whole range;
     checked on column spans (first, one that straddles a tile edge, last) for all rows."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "bigtile")
+    codes, scales = random_packed(N, K, "bigtile")
     rng = np.random.default_rng(12)
     z = np.zeros(scales.size, dtype=np.float16)
     pick = rng.random(scales.size) < 0.02
@@ -408,7 +428,7 @@ def test_matmul_streaming_more_row_tiles_than_one_round(gpu, ref):
     the CU count (a second round); checked on spans at both ends and in the middle."""
     torch, binding = gpu
     N, K = 30000, 512
-    codes, scales = synth.random_packed(N, K, "tall")
+    codes, scales = random_packed(N, K, "tall")
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     for M in (1, 3, 16):
         X = synth.activations(M, K, "tall", M)
@@ -424,7 +444,7 @@ def test_matmul_activation_magnitudes(gpu, ref, scale):
     |x| up to 16376): same relative accuracy on the streaming and the tiled path."""
     torch, binding = gpu
     N, K = 512, 2048
-    codes, scales = synth.random_packed(N, K, "mag")
+    codes, scales = random_packed(N, K, "mag")
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     for M in (1, 4, 8, 48):
         X = (synth.activations(M, K, "mag", M).astype(np.float32) * scale).astype(np.float16)
@@ -442,7 +462,7 @@ def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
     cases = [(1, 1000, 11008), (8, 272, 4096), (40, 512, 1024), (3, 4096, 11008), (1, 2048, 2048)]
     packed = {}
     for M, N, K in cases:
-        c, s = synth.random_packed(N, K, "ws")
+        c, s = random_packed(N, K, "ws")
         packed[(N, K)] = (to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)))
     xs = [to_dev(torch, synth.activations(M, K, "ws", i)) for i, (M, N, K) in enumerate(cases)]
     alone = [binding.itq3s_matmul(*packed[(N, K)], N, K, x) for (M, N, K), x in zip(cases, xs)]
@@ -461,7 +481,7 @@ def test_matmul_fp16_output_with_zero_points_in_most_blocks(gpu, ref, M, N, K):
     zero-point terms must be applied before the output is rounded -- subtracting them from an already
     rounded fp16 value costs up to 2^-11 of the much larger uncorrected sum (3e-3 of a row was seen)."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "zp16", M, z_fraction=0.9)
+    codes, scales = random_packed(N, K, "zp16", M, z_fraction=0.9)
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     X = synth.activations(M, K, "zp16", N)
     want = ref.matmul(codes, scales, N, K, X)
@@ -480,7 +500,7 @@ def test_calls_captured_in_a_graph_replay_like_eager(gpu, ref):
     cases = [(1, 272, K), (16, 100, 36864), (20, 300, K), (200, 300, K), (300, 2100, 512)]
     packed, xs = [], []
     for i, (M, N, Kc) in enumerate(cases):
-        c, s = synth.random_packed(N, Kc, "graph", i, z_fraction=0.02)
+        c, s = random_packed(N, Kc, "graph", i, z_fraction=0.02)
         packed.append((to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32))))
         xs.append(to_dev(torch, synth.activations(M, Kc, "graph", i)))
     group = [(packed[0][0], packed[0][1], 272), (packed[2][0], packed[2][1], 300)]
@@ -532,7 +552,7 @@ def test_matmul_from_two_host_threads(gpu, ref):
     cases = [(1, 1000, 4096), (8, 272, 4096), (20, 512, 1024), (200, 300, 2048), (3, 4096, 11008)]
     packed, xs = [], []
     for i, (M, N, K) in enumerate(cases):
-        c, s = synth.random_packed(N, K, "threads", i)
+        c, s = random_packed(N, K, "threads", i)
         packed.append((to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32))))
         xs.append(to_dev(torch, synth.activations(M, K, "threads", i)))
     alone = [binding.itq3s_matmul(*p, N, K, x) for (M, N, K), p, x in zip(cases, packed, xs)]
@@ -572,7 +592,7 @@ def test_matmul_few_tiles_long_k(gpu, ref, M, N, K):
     row without clearing, and every result equals the first bit for bit and the oracle within
     tolerance; one block in a hundred has a zero-point."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "fewtiles", M, z_fraction=0.01)
+    codes, scales = random_packed(N, K, "fewtiles", M, z_fraction=0.01)
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     X = synth.activations(M, K, "fewtiles", N)
     Xd = to_dev(torch, X)
@@ -595,7 +615,7 @@ def test_matmul_tiled_shapes_share_a_workspace(gpu, ref):
     cases = [(512, 384, 4096), (64, 2048, 1024), (300, 256, 2048), (17, 4096, 4096), (1024, 512, 2048), (512, 384, 4096)]
     packed, xs = [], []
     for i, (M, N, K) in enumerate(cases):
-        c, s = synth.random_packed(N, K, "tiled-ws", i)
+        c, s = random_packed(N, K, "tiled-ws", i)
         packed.append((to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32))))
         xs.append(to_dev(torch, synth.activations(M, K, "tiled-ws", i)))
     alone = [binding.itq3s_matmul(*pk, N, K, x) for (M, N, K), pk, x in zip(cases, packed, xs)]
@@ -612,7 +632,7 @@ def test_matmul_grouped_flags_and_determinism(gpu, ref):
     """The high-plane check covers every tensor of a grouped call; two identical calls give identical bits."""
     torch, binding = gpu
     K, Ns = 2048, [300, 4096, 48]
-    packed = [synth.random_packed(N, K, "grpflag", i) for i, N in enumerate(Ns)]
+    packed = [random_packed(N, K, "grpflag", i) for i, N in enumerate(Ns)]
     bad = packed[2][0].copy()
     bad[(2 * (K // 256) + 1) * 384 + 256 + 7] |= np.uint32(1 << 9)  # a high-plane bit in the last tensor
     X = to_dev(torch, synth.activations(2, K, "grpflag"))
@@ -632,7 +652,7 @@ def test_matmul_weight_side_matches_oracle(gpu, ref, M, N, K):
     """The paper's placement of the transform (inside the weight tile loader): same product, same bar;
     zero-points over the whole range are exact here (they only touch channel 0 of a block)."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "ws-side", z_fraction=0.02)
+    codes, scales = random_packed(N, K, "ws-side", z_fraction=0.02)
     rng = np.random.default_rng(13)
     z = (scales >> np.uint32(16)).astype(np.uint16).view(np.float16).copy()
     pick = rng.random(scales.size) < 0.01
@@ -645,7 +665,7 @@ def test_matmul_weight_side_matches_oracle(gpu, ref, M, N, K):
         flags = torch.zeros(1, dtype=torch.int32, device="cuda")
         got = binding.itq3s_matmul_weight_side(cd, sd, N, K, to_dev(torch, X), dtype=dtype, status_flags=flags).cpu().numpy()
         assert int(flags.item()) == 0
-        assert rel_rows(got, want) <= (MATMUL_TOL if dtype == torch.float32 else 2 * MATMUL_TOL)
+        assert rel_rows(got, want) <= MATMUL_TOL
 
 
 def test_matmul_weight_side_full_size_sampled(gpu, ref):
@@ -665,7 +685,7 @@ def test_matmul_weight_side_full_size_sampled(gpu, ref):
 
 def test_matmul_flags_high_plane(gpu, ref):
     torch, binding = gpu
-    codes, scales = synth.random_packed(64, 512, "hp")
+    codes, scales = random_packed(64, 512, "hp")
     bad = codes.copy()
     bad[384 * 3 + 256 + 77] |= np.uint32(1 << 20)
     for M in (1, 32):
@@ -697,7 +717,7 @@ def test_matmul_full_size_sampled_rows(gpu, ref, name, N, K, Ms):
     """The benchmark's shapes in the benchmark's launch configuration; the oracle recomputes a
     sample of 16-row ranges (first, last and random ones) for every activation row."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, name, z_fraction=0.001)
+    codes, scales = random_packed(N, K, name, z_fraction=0.001)
     for M in Ms:
         X = synth.activations(M, K, name, N)
         worst = run_matmul(torch, binding, ref, codes, scales, N, K, X, rows=sample_row_ranges(N, 6, N + K + M))
@@ -709,7 +729,7 @@ def test_matmul_prefill_full_size_sampled(gpu, ref, N, K, M):
     """The benchmark's prefill shapes and a few with 129..256 tiles (one workgroup per compute unit):
     sampled activation rows and weight-row ranges against the oracle, first and last tile included."""
     torch, binding = gpu
-    codes, scales = synth.random_packed(N, K, "prefill", z_fraction=0.001)
+    codes, scales = random_packed(N, K, "prefill", z_fraction=0.001)
     X = synth.activations(M, K, "prefill", N)
     cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
     Y = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), dtype=torch.float16)

@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 from paper_2603_27914_amd import synth
+from tests.packed_inputs import random_packed, unpack_numpy
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -29,25 +30,6 @@ def sylvester(n):
 
 def np_f16(word):
     return float(np.array([word & 0xFFFF], dtype=np.uint16).view(np.float16)[0])
-
-
-def unpack_numpy(codes, scales, N, K):
-    """Second implementation of the storage layout, written from its description alone.
-    -> (c int64 [N,K], d float64 [N,KB], z float64 [N,KB])."""
-    KB, NT = K // 256, (N + 15) // 16
-    t = codes.reshape(NT, KB, 384)
-    e = np.arange(256)
-    lane_g, i = e >> 6, e & 63
-    c = np.zeros((NT * 16, K), dtype=np.int64)
-    for r in range(16):
-        lane = 16 * lane_g + r
-        lo = (t[:, :, 4 * lane + (i >> 4)] >> (2 * (i & 15)).astype(np.uint32)) & 3
-        hi = (t[:, :, 256 + 2 * lane + (i >> 5)] >> (i & 31).astype(np.uint32)) & 1
-        c[r::16, :] = (lo | (hi << 2)).reshape(NT, K)
-    s = scales.reshape(NT, KB, 16).transpose(0, 2, 1).reshape(NT * 16, KB)
-    d = (s & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float64)
-    z = (s >> 16).astype(np.uint16).view(np.float16).astype(np.float64)
-    return c[:N], d[:N], z[:N]
 
 
 # ------------------------------------------------------------------------------ transform pins
@@ -198,6 +180,38 @@ def test_quantize_block_against_definition(ref, seed):
     assert set(np.unique(codes)) <= {0, 1, 2}
 
 
+def test_literal_rounding_formula_against_exact_thresholds(ref, capsys):
+    """Def. 1 as printed, clamp(floor(w'/d + z + 1/2), -1, 1), evaluated literally in fp64 (one
+    division, two additions, each rounded) against the oracle's exact comparison with the two
+    thresholds (+-1/2 - z) d.  They may differ only where the literal form's own rounding moves a
+    value across an integer, i.e. within a few ulp of a decision point; the count of such elements
+    is printed (it is reported, not hidden behind a mask)."""
+    rng = np.random.default_rng(12)
+    n_blocks, differ, near, total = 3000, 0, 0, 0
+    for i in range(n_blocks):
+        w = (0.02 * rng.standard_t(4.0, size=256)).astype(np.float32)
+        if i % 3 == 0:
+            w[0] = np.float32(rng.normal() * 0.5)  # zero-points of both signs
+        codes, word, flags = ref.quantize_block(w)
+        d, z = np_f16(word), np_f16(word >> 16)
+        if d == 0.0:
+            continue
+        wt = ref.forward_block(w)
+        x = wt / d + z + 0.5  # fp64, every operation rounded: the literal formula
+        q = np.clip(np.floor(x), -1, 1).astype(np.int64)
+        bad = q != codes.astype(np.int64) - 1
+        # distance of the exact quotient from the nearest decision point, in units of d
+        exact = wt.astype(np.longdouble) / np.longdouble(d) + np.longdouble(z) + np.longdouble(0.5)
+        dist = np.abs(exact - np.round(exact))
+        assert np.all(dist[bad] < 4 * np.finfo(np.float64).eps * np.maximum(1.0, np.abs(x[bad]))), "a disagreement far from any threshold"
+        differ += int(bad.sum())
+        near += int((dist < 1e-12).sum())
+        total += 256
+    with capsys.disabled():
+        print("\n[P12] literal Def. 1 vs exact thresholds: %d of %d elements differ (%d within 1e-12 of a decision point)" % (differ, total, near))
+    assert differ <= near
+
+
 def test_quantize_threshold_ties(ref):
     """Half-up rounding of Def. 1: a coefficient exactly on (0.5 - z) d goes to +1, one exactly on
     (-0.5 - z) d stays 0.  Built in the transform domain with integer-valued data so that the
@@ -328,7 +342,7 @@ def test_dequantize_against_dense_definition(ref):
 
 
 def test_bad_code_is_flagged(ref):
-    codes, scales = synth.random_packed(16, 256, "bad")
+    codes, scales = random_packed(16, 256, "bad")
     _, flags = ref.dequantize(codes, scales, 16, 256, return_flags=True)
     assert flags == 0
     bad = codes.copy()
