@@ -7,9 +7,9 @@
  * zero-point z = 100 bytes (Sec. 4.1).  Reconstruction is w_hat = H( d (q - z) ) (Prop. 1).
  *
  * Conventions for every call below
- *   - all data pointers are DEVICE pointers owned by the caller; the library never allocates,
- *     frees or synchronises.  Work is enqueued on `stream` (a hipStream_t passed as void*; NULL =
- *     the default stream) and the call returns at once.
+ *   - all data pointers are DEVICE pointers owned by the caller; the calls declared in this header
+ *     never allocate, free or synchronise.  Work is enqueued on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and the call returns at once.
  *   - the return value is 0 (ITQ3S_OK) or a negative ITQ3S_ERR_* code.  Argument errors are found
  *     on the host before anything is launched; then no kernel runs and no memory is touched.
  *   - `status_flags` (may be NULL) is one device uint32 into which kernels OR data-condition bits
@@ -61,16 +61,19 @@ extern "C" {
 #define ITQ3S_FLAG_BAD_CODE 8u  /* decode: a code outside {0,1,2} was met (dequantize checks both
                                    planes; matmul checks the high plane only and treats a low-plane
                                    3 as digit +2)                                                  */
+#define ITQ3S_FLAG_ACT_RANGE 16u /* matmul: a rotated activation left the fp16 range (see itq3s_matmul);
+                                   the outputs that depend on that 256-channel chunk are Inf or NaN */
 
 /* Sizes of the two packed arrays for W[N,K]: NT*KB*1536 and NT*KB*64 bytes (0 if K % 256 != 0). */
 size_t itq3s_codes_bytes(int64_t N, int64_t K);
 size_t itq3s_scales_bytes(int64_t N, int64_t K);
 
-/* Bytes of scratch itq3s_matmul needs for the rotated activations (Sec. 2.3: H is symmetric and
- * its own inverse, so <H v, x> = <v, H x>; the library rotates X once per call instead of every
- * weight block).  Never 0; grows with M*K.  For M > 16 and shapes with few output tiles (at most 128
- * tiles of 128 x 256) it also covers the partial sums of the workgroups that share a tile's K range
- * (up to 8 x M x N x 4 bytes, tiles rounded up). */
+/* Bytes of scratch itq3s_matmul needs (Sec. 2.3: H is symmetric and its own inverse, so
+ * <H v, x> = <v, H x>; the library rotates X once per call instead of every weight block).  Never 0.
+ * M <= 4: 256 (the streaming kernel rotates inside the kernel; the workspace is not touched).
+ * Larger M: room for the rotated activations, grows with M*K; for M > 16 and shapes with few output
+ * tiles (at most 128 tiles of 128 x 256) also the partial sums of the workgroups that share a tile's
+ * K range (up to 8 x M x N x 4 bytes, tiles rounded up).  A function of the three sizes only. */
 size_t itq3s_matmul_workspace_bytes(int64_t M, int64_t N, int64_t K);
 
 /* Offline quantization (Alg. 1, Def. 1).  Per block: w' = H w in fp64 (butterfly stages
@@ -95,8 +98,15 @@ int itq3s_dequantize(const uint32_t *codes, const uint32_t *scales, int64_t N, i
 /* Fused matmul (problem statement of Alg. 2; Sec. 5.4 for M = 1):  Y[m][n] = sum_k X[m][k] w_hat[n][k].
  * No dequantized weight is written to memory.  M <= 16 takes the bandwidth-bound streaming path
  * (M <= 32: two passes of it), larger M the tiled MFMA path (which accepts K <= 4194304 only:
- * ITQ3S_ERR_SHAPE beyond); fp32 accumulation in both, the zero-point terms included: an output
- * element is rounded once.
+ * ITQ3S_ERR_SHAPE beyond; the streaming path K <= 2^28); fp32 accumulation in both, the zero-point
+ * terms included: an output element is rounded once.
+ * Activation range.  Every 256-channel chunk x of a row of X is replaced by x~ = H x, rounded to
+ * fp16, after an intermediate T = X_16x16 H_16 / 4 that is split into fp16 parts.  Both stay
+ * finite whenever  max|x| <= 16376  and  |(H x)_k| <= 65504  over the chunk (the second holds if
+ * sum|x| <= 16 * 65504; any chunk with max|x| <= 4094 satisfies both).  Outside that range the
+ * products that involve the chunk are Inf/NaN although the exact result is finite, and
+ * ITQ3S_FLAG_ACT_RANGE is OR-ed into status_flags.  Scale such activations down by a power of
+ * two (the product is linear) before the call.
  *   X  [in]  device, M x K fp16 row-major, row stride ldx elements (ldx >= K, ldx % 8 == 0,
  *            pointer 16-byte aligned)
  *   Y  [out] device, M x N of y_dtype, row stride ldy elements (ldy >= N); overwritten
@@ -115,7 +125,8 @@ int itq3s_matmul(const uint32_t *codes, const uint32_t *scales, int64_t N, int64
  *   w  [in] HOST array of count descriptors (read during the call, not kept): device pointers codes,
  *           scales (as for itq3s_matmul), rows N, output Y (M x N of y_dtype, row stride ldy >= N)
  *   X, M, ldx, y_dtype, status_flags, stream: as for itq3s_matmul
- *   workspace: at least itq3s_matmul_workspace_bytes(M, max N, K) */
+ *   workspace: at least the largest itq3s_matmul_workspace_bytes(M, N_t, K) over the tensors of the call
+ *           (ITQ3S_ERR_WORKSPACE otherwise: how a tensor is computed never depends on the room given) */
 #define ITQ3S_MAX_GROUP 4
 typedef struct itq3s_weight {
     const uint32_t *codes;
@@ -134,10 +145,9 @@ int itq3s_matmul_grouped(const itq3s_weight *w, int count, int64_t K, const void
  * agree with itq3s_matmul within the same tolerance (the rounding sits on w_hat instead of H x).  It
  * repeats the transform for every 128-row slab of X and is meant for comparing the two placements,
  * not as the fast path.  Arguments as for itq3s_matmul; any M with ceil(M/128) <= 65535.
- * kernel_ms (HOST pointer, may be NULL): if given, the call waits and stores the kernel's duration. */
+ * (A variant that also reports the kernel's duration is declared in itq3s_bench.h.) */
 int itq3s_matmul_weight_side(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
-                             int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags, void *stream,
-                             float *kernel_ms);
+                             int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags, void *stream);
 
 /* Block-size ablation (Sec. 6, "Ablation: FWHT Block Size"): rotate, quantize and reconstruct with a
  * transform length block_size in {32, 64, 128, 256, 512} instead of the format's 256, without
@@ -159,27 +169,6 @@ int itq3s_matmul_weight_side(const uint32_t *codes, const uint32_t *scales, int6
  * Returns ITQ3S_ERR_SHAPE for any other block_size. */
 int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block_size, uint8_t *codes_out, uint32_t *scales_out,
                     float *W_hat, int64_t ldo, double *err2, uint32_t *status_flags, void *stream);
-
-/* Measurement aids: itq3s_matmul / itq3s_matmul_grouped with the same arguments, after which the call
- * WAITS for the work and stores in *kernel_ms (HOST pointer) the duration of the contraction kernel
- * alone (the streaming kernel for M <= 16, its first pass for M <= 32; for larger M the first tiled launch; not the
- * activation-rotation launch in front of it, not the launch that adds up partial sums behind it for
- * shapes with few tiles, not launch gaps), taken from HIP events attached to
- * that kernel's dispatch.  They create and destroy two events per call: not for production loops,
- * not capturable in a graph. */
-int itq3s_matmul_timed(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
-                       int64_t ldx, void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes,
-                       uint32_t *status_flags, void *stream, float *kernel_ms);
-
-int itq3s_matmul_grouped_timed(const itq3s_weight *w, int count, int64_t K, const void *X, int64_t M, int64_t ldx,
-                               int y_dtype, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
-                               void *stream, float *kernel_ms);
-
-/* Measurement aid: a plain streaming read of `bytes` bytes (rounded down to a multiple of 16) of device
- * memory at src (16-byte aligned), nothing else -- the time such a launch takes is the practical floor
- * for a streaming matmul over the same bytes.  sink: one device uint32 (written only for one
- * particular checksum of the data; present so that the reads cannot be optimised away). */
-int itq3s_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream);
 
 /* Static text for a status code.  Never NULL. */
 const char *itq3s_strerror(int status);

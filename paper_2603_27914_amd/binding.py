@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libitq3s.so")
 
 F32, F16 = 0, 1
-FLAG_NONFINITE, FLAG_SCALE_SAT, FLAG_Z_CLAMP, FLAG_BAD_CODE = 1, 2, 4, 8
+FLAG_NONFINITE, FLAG_SCALE_SAT, FLAG_Z_CLAMP, FLAG_BAD_CODE, FLAG_ACT_RANGE = 1, 2, 4, 8, 16
 
 EXPORTS = [
     "itq3s_codes_bytes",
@@ -27,6 +27,7 @@ EXPORTS = [
     "itq3s_matmul_grouped_timed",
     "itq3s_matmul_timed",
     "itq3s_matmul_weight_side",
+    "itq3s_matmul_weight_side_timed",
     "itq3s_read_probe",
     "itq3s_strerror",
     "itq3s_version",
@@ -77,7 +78,9 @@ def lib():
         L.itq3s_matmul_timed.restype = ci
         L.itq3s_matmul_timed.argtypes = L.itq3s_matmul.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_matmul_weight_side.restype = ci
-        L.itq3s_matmul_weight_side.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp, ctypes.POINTER(ctypes.c_float)]
+        L.itq3s_matmul_weight_side.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp]
+        L.itq3s_matmul_weight_side_timed.restype = ci
+        L.itq3s_matmul_weight_side_timed.argtypes = L.itq3s_matmul_weight_side.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.itq3s_read_probe.restype = ci
         L.itq3s_read_probe.argtypes = [vp, sz, vp, vp]
         L.itq3s_strerror.restype = ctypes.c_char_p
@@ -104,6 +107,29 @@ def _need_cuda(*tensors):
     for t in tensors:
         if t is not None and not t.is_cuda:
             raise Itq3sError("libitq3s works on device memory only; got a CPU tensor")
+
+
+def _need_packed(codes, scales, N, K, *others):
+    """The C ABI sees pointers, not sizes: refuse here what would make a kernel read outside the
+    packed arrays (a wrong N or K, a slice, a tensor of another type or on another device)."""
+    cb, sb = itq3s_codes_bytes(N, K), itq3s_scales_bytes(N, K)
+    if cb == 0:
+        raise Itq3sError("bad shape: N and K must be positive, K a multiple of 256")
+    for name, t, nbytes in (("codes", codes, cb), ("scales", scales, sb)):
+        if t.dtype != torch.int32 or not t.is_contiguous():
+            raise Itq3sError("%s must be a contiguous int32 tensor" % name)
+        if t.numel() * 4 < nbytes:
+            raise Itq3sError("%s holds %d bytes, W[%d, %d] needs %d" % (name, t.numel() * 4, N, K, nbytes))
+        if t.device != codes.device:
+            raise Itq3sError("codes and scales must be on the same device")
+    for t in others:
+        if t is not None and t.device != codes.device:
+            raise Itq3sError("every tensor of a call must be on the same device")
+
+
+def _need_flags(status_flags):
+    if status_flags is not None and (status_flags.dtype != torch.int32 or status_flags.numel() < 1 or not status_flags.is_contiguous()):
+        raise Itq3sError("status_flags must be a contiguous int32 tensor with at least one element")
 
 
 def itq3s_codes_bytes(N, K):
@@ -138,6 +164,8 @@ def itq3s_quantize(W, codes=None, scales=None, status_flags=None):
     N, K = W.shape
     if codes is None or scales is None:
         codes, scales = alloc_packed(N, K, W.device)
+    _need_packed(codes, scales, N, K, W, status_flags)
+    _need_flags(status_flags)
     _check(lib().itq3s_quantize(_ptr(W), N, K, W.stride(0), _ptr(codes), _ptr(scales), _ptr(status_flags), _stream()))
     return codes, scales
 
@@ -145,6 +173,8 @@ def itq3s_quantize(W, codes=None, scales=None, status_flags=None):
 def itq3s_dequantize(codes, scales, N, K, out=None, dtype=torch.float32, status_flags=None):
     """-> reconstructed weights [N, K] (float32 or float16) on the device."""
     _need_cuda(codes, scales, out, status_flags)
+    _need_packed(codes, scales, N, K, out, status_flags)
+    _need_flags(status_flags)
     if out is None:
         out = torch.empty((N, K), dtype=dtype, device=codes.device)
     if out.dtype not in (torch.float32, torch.float16) or out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (N, K):
@@ -201,6 +231,8 @@ def itq3s_matmul_weight_side(codes, scales, N, K, X, out=None, dtype=torch.float
     """Y = X @ W_hat^T with the inverse transform inside the weight tile loader (the paper's placement).
     timed=True waits and returns (Y, kernel milliseconds)."""
     _need_cuda(codes, scales, X, out, status_flags)
+    _need_packed(codes, scales, N, K, X, out, status_flags)
+    _need_flags(status_flags)
     if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
         raise Itq3sError("X must be float16 [M, K] with unit column stride")
     M = X.shape[0]
@@ -209,13 +241,18 @@ def itq3s_matmul_weight_side(codes, scales, N, K, X, out=None, dtype=torch.float
     if out.dtype not in (torch.float32, torch.float16) or out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (M, N):
         raise Itq3sError("out must be float32/float16 [M, N] with unit column stride")
     ms = ctypes.c_float(0.0)
-    _check(
-        lib().itq3s_matmul_weight_side(
-            _ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
-            out.stride(0), _ptr(status_flags), _stream(), ctypes.byref(ms) if timed else None,
-        )
-    )
-    return (out, float(ms.value)) if timed else out
+    args = (_ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
+            out.stride(0), _ptr(status_flags), _stream())
+    if timed:
+        _check(lib().itq3s_matmul_weight_side_timed(*args, ctypes.byref(ms)))
+        return out, float(ms.value)
+    _check(lib().itq3s_matmul_weight_side(*args))
+    return out
+
+
+def itq3s_matmul_weight_side_timed(codes, scales, N, K, X, out=None, dtype=torch.float32, status_flags=None):
+    """itq3s_matmul_weight_side, then wait; -> (Y, milliseconds the kernel ran by the GPU's clock)."""
+    return itq3s_matmul_weight_side(codes, scales, N, K, X, out, dtype, status_flags, timed=True)
 
 
 def itq3s_read_probe(buf, sink):
@@ -233,6 +270,7 @@ def itq3s_matmul_grouped_timed(weights, K, X, outs=None, dtype=torch.float32, wo
 
 def itq3s_matmul_grouped(weights, K, X, outs=None, dtype=torch.float32, workspace=None, status_flags=None, _timed=None):
     """weights: list of (codes, scales, N) sharing K -> list of Y_t[M, N_t] = X @ W_hat_t^T, one call."""
+    _need_cuda(X, workspace, status_flags)
     M = X.shape[0]
     if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
         raise Itq3sError("X must be float16 [M, K] with unit column stride")
@@ -242,15 +280,17 @@ def itq3s_matmul_grouped(weights, K, X, outs=None, dtype=torch.float32, workspac
         outs = [torch.empty((M, N), dtype=dtype, device=X.device) for _, _, N in weights]
     if len(outs) != len(weights) or len({o.dtype for o in outs}) != 1 or outs[0].dtype not in (torch.float32, torch.float16):
         raise Itq3sError("outs: one float32/float16 tensor per weight tensor, all of one dtype")
+    _need_flags(status_flags)
     arr = (Weight * len(weights))()
     for i, ((codes, scales, N), out) in enumerate(zip(weights, outs)):
         _need_cuda(codes, scales, out)
+        _need_packed(codes, scales, N, K, X, out, workspace, status_flags)
         if out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (M, N):
             raise Itq3sError("out %d must be [M, N] with unit column stride" % i)
         arr[i] = Weight(codes.data_ptr(), scales.data_ptr(), N, out.data_ptr(), out.stride(0))
     _need_cuda(X, workspace, status_flags)
     if workspace is None:
-        workspace = torch.empty(itq3s_matmul_workspace_bytes(M, max(N for _, _, N in weights), K), dtype=torch.uint8, device=X.device)
+        workspace = torch.empty(max(itq3s_matmul_workspace_bytes(M, N, K) for _, _, N in weights), dtype=torch.uint8, device=X.device)
     args = (
         arr, len(weights), K, _ptr(X), M, X.stride(0), F16 if outs[0].dtype == torch.float16 else F32,
         _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(status_flags), _stream(),
@@ -272,6 +312,8 @@ def itq3s_matmul_timed(codes, scales, N, K, X, out=None, dtype=torch.float32, wo
 def itq3s_matmul(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None, _timed=None):
     """Y[M, N] = X[M, K] @ W_hat[N, K]^T from the packed weights.  X: float16 device tensor."""
     _need_cuda(codes, scales, X, out, workspace, status_flags)
+    _need_packed(codes, scales, N, K, X, out, workspace, status_flags)
+    _need_flags(status_flags)
     if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
         raise Itq3sError("X must be float16 [M, K] with unit column stride")
     M = X.shape[0]

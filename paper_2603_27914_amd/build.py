@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libitq3s.so")
-SOURCES = ["itq3s_api.hip", "itq3s_quantize.hip", "itq3s_dequantize.hip", "itq3s_rotate.hip", "itq3s_gemv.hip", "itq3s_gemm.hip", "itq3s_gemm_ws.hip", "itq3s_probe.hip", "itq3s_ablation.hip"]
+SOURCES = ["itq3s_api.hip", "itq3s_quantize.hip", "itq3s_dequantize.hip", "itq3s_rotate.hip", "itq3s_gemv.hip", "itq3s_gemv_rows.hip", "itq3s_gemm.hip", "itq3s_gemm_ws.hip", "itq3s_probe.hip", "itq3s_ablation.hip"]
 FLAGS = [
     "--offload-arch=gfx950",
     "-O3",
@@ -23,7 +23,7 @@ FLAGS = [
 def build_lib(force=True, verbose=False):
     """Compile every kernel source and link the shared library.  Returns its path."""
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")] + [os.path.join(HERE, "..", "include", "itq3s.h")]
+    deps = srcs + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")] + [os.path.join(HERE, "..", "include", h) for h in ("itq3s.h", "itq3s_bench.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     objs = []

@@ -1,6 +1,7 @@
 // C-ABI entry points of libitq3s: argument validation on the host, then launches.  See
-// include/itq3s.h for the contract of every call.
+// include/itq3s.h for the contract of every call (include/itq3s_bench.h for the measurement aids).
 #include "../../include/itq3s.h"
+#include "../../include/itq3s_bench.h"
 #include "itq3s_kernels.h"
 
 namespace {
@@ -24,9 +25,14 @@ constexpr int64_t kChunkedMaxM = 2 * itq3s::kGemvMaxM;  // up to here M > 16 run
 WorkspacePlan plan_workspace(int64_t M, int64_t N, int64_t K) {
     if (M > itq3s::kGemvMaxM && M <= kChunkedMaxM) return plan_workspace(itq3s::kGemvMaxM, N, K);
     WorkspacePlan p;
+    if (M <= itq3s::kGemvFusedMaxM) {  // the streaming kernel rotates the activations itself: nothing to park
+        p.xt_bytes = p.s_bytes = p.flag_bytes = p.partial_bytes = 0;
+        p.total = 256;
+        return p;
+    }
     const int64_t rows = M <= itq3s::kGemvMaxM ? pad_m(M) : M;
     p.xt_bytes = round_up((size_t)rows * (size_t)K * 2, 256);
-    // streaming path without in-kernel rotation: two sums per (block, row), see launch_rotate_frag
+    // streaming path with a rotation launch: two sums per (block, row), see launch_rotate_frag
     p.s_bytes = M <= itq3s::kGemvMaxM ? round_up((size_t)rows * (size_t)(K / 256) * 8, 256) : 0;
     // tiled path: split-K flags, then the shares (layout: rotated activations | flags | shares)
     p.flag_bytes = M <= itq3s::kGemvMaxM ? 0 : 512;
@@ -35,6 +41,29 @@ WorkspacePlan plan_workspace(int64_t M, int64_t N, int64_t K) {
     return p;
 }
 
+}  // namespace
+
+namespace {
+// a call with a pair of events armed for the contraction kernel's dispatch, then a wait
+template <typename Call>
+int timed(float* kernel_ms, Call call) {
+    if (!kernel_ms) return ITQ3S_ERR_NULL;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return ITQ3S_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return ITQ3S_ERR_LAUNCH;
+    }
+    itq3s::set_launch_timing(e0, e1);
+    int rc = call();
+    const bool taken = itq3s::take_launch_timing().start == nullptr;  // (also disarms if validation returned before any launch)
+    if (rc == ITQ3S_OK && taken) {
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(kernel_ms, e0, e1) != hipSuccess) rc = ITQ3S_ERR_LAUNCH;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
 }  // namespace
 
 extern "C" {
@@ -96,15 +125,17 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
     if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
     if (M > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
     if (M > itq3s::kGemvMaxM && K > (1LL << 22)) return ITQ3S_ERR_SHAPE;  // the tiled kernel's 32-bit byte offsets
-    int64_t n_max = 0;
+    if (K > (1LL << 28) || (M <= itq3s::kGemvFusedMaxM && (M - 1) * ldx + K > (1LL << 29))) return ITQ3S_ERR_SHAPE;  // 32-bit byte offsets of the streaming kernel
+    size_t need = 0;
     for (int i = 0; i < count; ++i) {
         if (!w[i].codes || !w[i].scales || !w[i].Y) return ITQ3S_ERR_NULL;
         if (w[i].N <= 0 || w[i].ldy < w[i].N || (w[i].N + 15) / 16 > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
         if (!aligned(w[i].codes, 16) || !aligned(w[i].scales, 16) || !aligned(w[i].Y, y_dtype == ITQ3S_F16 ? 2 : 4)) return ITQ3S_ERR_ALIGN;
-        if (w[i].N > n_max) n_max = w[i].N;
+        const size_t need_i = itq3s_matmul_workspace_bytes(M, w[i].N, K);
+        if (need_i > need) need = need_i;
     }
     if (!aligned(X, 16) || ldx % 8 != 0 || (status_flags && !aligned(status_flags, 4))) return ITQ3S_ERR_ALIGN;
-    if (!workspace || workspace_bytes < itq3s_matmul_workspace_bytes(M, n_max, K)) return ITQ3S_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < need) return ITQ3S_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return ITQ3S_ERR_ALIGN;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -125,27 +156,27 @@ int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void
         }
         return ITQ3S_OK;
     }
-    const WorkspacePlan p = plan_workspace(M, n_max, K);
+    const WorkspacePlan p = plan_workspace(M, w[0].N, K);  // (the parts in front of the split-K shares do not depend on N)
     _Float16* Xt = static_cast<_Float16*>(workspace);
     const _Float16* Xh = static_cast<const _Float16*>(X);
     const int y_f16 = y_dtype == ITQ3S_F16;
     if (M <= itq3s::kGemvMaxM) {
         itq3s::GemvWeight gw[ITQ3S_MAX_GROUP];
         for (int i = 0; i < count; ++i) gw[i] = itq3s::GemvWeight{w[i].codes, w[i].scales, w[i].N, w[i].Y, w[i].ldy};
-        const int MP = pad_m(M);
-        if (itq3s::gemv_can_fuse(M, K)) return itq3s::launch_gemv(gw, count, K, Xh, ldx, nullptr, M, MP, true, y_f16, status_flags, st);
+        if (M <= itq3s::kGemvFusedMaxM) return itq3s::launch_gemv(gw, count, K, Xh, ldx, M, y_f16, status_flags, st);
+        const int MP = pad_m(M) < 8 ? 8 : pad_m(M);
         float* S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.xt_bytes);
-        int rc = itq3s::launch_rotate_frag(Xh, M, K, ldx, MP, Xt, S, st);
+        int rc = itq3s::launch_rotate_frag(Xh, M, K, ldx, MP, Xt, S, status_flags, st);
         if (rc != 0) return rc;
-        return itq3s::launch_gemv(gw, count, K, Xt, 0, S, M, MP, false, y_f16, status_flags, st);
+        return itq3s::launch_gemv_rows(gw, count, K, Xt, S, M, MP, y_f16, status_flags, st);
     }
     // tiled path: one rotation, then one contraction launch per tensor
     unsigned char* const base = static_cast<unsigned char*>(workspace);
     uint32_t* zflags = reinterpret_cast<uint32_t*>(base + p.xt_bytes);
     float* partial = reinterpret_cast<float*>(base + p.xt_bytes + p.flag_bytes);
-    const size_t partial_room = workspace_bytes - p.xt_bytes - p.flag_bytes;  // (a tensor whose shares do not fit runs unsplit)
+    const size_t partial_room = workspace_bytes - p.xt_bytes - p.flag_bytes;  // (checked above: every tensor's shares fit)
     static_assert(itq3s::kGemmFlagWords * 4 <= 512, "flag words fit their slot");
-    int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, zflags, itq3s::kGemmFlagWords, st);
+    int rc = itq3s::launch_rotate_rowmajor(Xh, M, K, ldx, Xt, zflags, itq3s::kGemmFlagWords, status_flags, st);
     for (int i = 0; i < count && rc == 0; ++i) {
         rc = itq3s::launch_gemm(w[i].codes, w[i].scales, w[i].N, K, Xt, Xh, ldx, M, w[i].Y, y_f16, w[i].ldy, partial, partial_room, zflags,
                                 status_flags, st);
@@ -164,7 +195,7 @@ int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64
 }
 
 int itq3s_matmul_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
-                             void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream, float* kernel_ms) {
+                             void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream) {
     if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
     if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
     if ((N + 15) / 16 > 0x7fffffffLL / (K / 256) || (M + 127) / 128 > 65535) return ITQ3S_ERR_SHAPE;
@@ -172,44 +203,22 @@ int itq3s_matmul_weight_side(const uint32_t* codes, const uint32_t* scales, int6
     if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) ||
         (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (kernel_ms) {
-        if (hipEventCreate(&e0) != hipSuccess) return ITQ3S_ERR_LAUNCH;
-        if (hipEventCreate(&e1) != hipSuccess) {
-            (void)hipEventDestroy(e0);
-            return ITQ3S_ERR_LAUNCH;
-        }
-        itq3s::set_launch_timing(e0, e1);
-    }
-    int rc = itq3s::launch_gemm_weight_side(codes, scales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags, st);
-    if (kernel_ms) {
-        (void)itq3s::take_launch_timing();
-        if (rc == ITQ3S_OK && (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(kernel_ms, e0, e1) != hipSuccess)) rc = ITQ3S_ERR_LAUNCH;
-        (void)hipEventDestroy(e0);
-        (void)hipEventDestroy(e1);
-    }
-    return rc;
+    return itq3s::launch_gemm_weight_side(codes, scales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags,
+                                          static_cast<hipStream_t>(stream));
+}
+
+// ---- measurement aids (include/itq3s_bench.h): the same calls with a pair of events armed for the
+// contraction kernel's dispatch, then a wait
+
+
+int itq3s_matmul_weight_side_timed(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
+                                   void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream, float* kernel_ms) {
+    return timed(kernel_ms, [&] { return itq3s_matmul_weight_side(codes, scales, N, K, X, M, ldx, Y, y_dtype, ldy, status_flags, stream); });
 }
 
 int itq3s_matmul_grouped_timed(const itq3s_weight* w, int count, int64_t K, const void* X, int64_t M, int64_t ldx, int y_dtype,
                                void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream, float* kernel_ms) {
-    if (!kernel_ms) return ITQ3S_ERR_NULL;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (hipEventCreate(&e0) != hipSuccess) return ITQ3S_ERR_LAUNCH;
-    if (hipEventCreate(&e1) != hipSuccess) {
-        (void)hipEventDestroy(e0);
-        return ITQ3S_ERR_LAUNCH;
-    }
-    itq3s::set_launch_timing(e0, e1);
-    int rc = itq3s_matmul_grouped(w, count, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream);
-    const bool taken = itq3s::take_launch_timing().start == nullptr;  // (also disarms if validation returned before any launch)
-    if (rc == ITQ3S_OK && taken) {
-        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(kernel_ms, e0, e1) != hipSuccess) rc = ITQ3S_ERR_LAUNCH;
-    }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    return rc;
+    return timed(kernel_ms, [&] { return itq3s_matmul_grouped(w, count, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream); });
 }
 
 int itq3s_matmul_timed(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,

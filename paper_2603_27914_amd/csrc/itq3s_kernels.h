@@ -7,10 +7,12 @@
 
 namespace itq3s {
 
-constexpr uint32_t kFlagNonFinite = 1u, kFlagScaleSat = 2u, kFlagZClamp = 4u, kFlagBadCode = 8u;
+constexpr uint32_t kFlagNonFinite = 1u, kFlagScaleSat = 2u, kFlagZClamp = 4u, kFlagBadCode = 8u, kFlagActRange = 16u;
 
 // Streaming path handles up to this many activation rows; more rows go to the tiled MFMA path.
 constexpr int kGemvMaxM = 16;
+// Up to this many rows the streaming kernel rotates the activations itself (one launch, no workspace).
+constexpr int kGemvFusedMaxM = 4;
 // One streaming launch serves up to this many weight tensors that share K and the activations.
 constexpr int kGemvMaxGroup = 4;
 
@@ -30,17 +32,16 @@ int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t*
 int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* out, int out_f16, int64_t ldo,
                       uint32_t* flags, hipStream_t stream);
 
-// Rotated activations for the streaming path: Xt in MFMA operand order with MP (power of two >= M,
-// <= 16) columns; S[b*MP + m] = sum over the rounded rotated chunk, S[KB*MP + b*MP + m] = the exact
-// sum of the unrounded one, 16 x[m][256 b].
-int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, hipStream_t stream);
+// Rotated activations for the streaming path with 5..16 rows: Xt in MFMA operand order with MP (8 or
+// 16) columns; S[b*MP + m] = sum over the rounded rotated chunk, S[KB*MP + b*MP + m] = the exact
+// sum of the unrounded one, 16 x[m][256 b].  flags (may be null): kFlagActRange is OR-ed in if a
+// rotated value leaves the fp16 range.
+int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, uint32_t* flags, hipStream_t stream);
 
 // Rotated activations for the tiled path: Xt[m][k] row-major, row stride K.
 // (also clears n_zero words at zero_words: the split-K flags of the contraction that follows)
-int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, uint32_t* zero_words, int n_zero, hipStream_t stream);
-
-// True if the streaming kernel can rotate the activations itself (one launch, no workspace use).
-bool gemv_can_fuse(int64_t M, int64_t K);
+int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, uint32_t* zero_words, int n_zero, uint32_t* flags,
+                           hipStream_t stream);
 
 // One weight tensor of a streaming launch and where its product goes.
 struct GemvWeight {
@@ -51,11 +52,18 @@ struct GemvWeight {
     int64_t ldy;
 };
 
-// count (1..kGemvMaxGroup) tensors W_t[N_t, K] against the same activations in one launch.
-// fused: X = activations [M][ldx], S unused.  Otherwise X = rotated activations in operand order with
-// MP columns (from launch_rotate_frag), ldx unused, S = their block sums.
-int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, const float* S, int64_t M, int MP, bool fused,
-                int y_f16, uint32_t* flags, hipStream_t stream);
+// count (1..kGemvMaxGroup) tensors W_t[N_t, K] against the same activations X[M][ldx], M <= kGemvFusedMaxM,
+// in one launch that rotates the activations itself.
+int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, int64_t M, int y_f16, uint32_t* flags,
+                hipStream_t stream);
+
+// The same for kGemvFusedMaxM < M <= kGemvMaxM: Xt = rotated activations in operand order with MP
+// columns and S = their block sums, both from launch_rotate_frag.
+int launch_gemv_rows(const GemvWeight* w, int count, int64_t K, const _Float16* Xt, const float* S, int64_t M, int MP, int y_f16,
+                     uint32_t* flags, hipStream_t stream);
+
+// Compute units of the current device (cached).
+int cu_count();
 
 // Tiled matmul, M > 16.  Xt = rotated activations (launch_rotate_rowmajor); X, ldx = the activations
 // themselves (zero-point term).  Shapes with few output tiles split K over several workgroups per tile

@@ -2,7 +2,7 @@
 // It moves the same bytes as a streaming-matmul launch and nothing else, so its duration is the
 // practical floor (launch latency + memory pipeline) that the contraction kernels are judged against
 // next to the 8 TB/s data-sheet figure.
-#include "../../include/itq3s.h"
+#include "../../include/itq3s_bench.h"
 #include "itq3s_dev.h"
 #include "itq3s_kernels.h"
 

@@ -18,7 +18,9 @@ namespace itq3s {
 
 // x~ = H x for one chunk.  Lane l reads x[16 (l%16) + 4 (l/16) + 0..3] and returns the rounded
 // elements e = 64 (l/16) + 16 i + l%16, i = 0..3.
-__device__ __forceinline__ void rotate_chunk(const _Float16* __restrict__ src, int lane, _Float16 out[4]) {
+// Returns false if a rotated value (or the intermediate T, which then turns the result into NaN)
+// leaves the fp16 range.
+__device__ __forceinline__ bool rotate_chunk(const _Float16* __restrict__ src, int lane, _Float16 out[4]) {
     const int r16 = lane & 15, g = lane >> 4;
     half4 h, q;  // H_16[4g + j][r16] and a quarter of it
 #pragma unroll
@@ -38,8 +40,13 @@ __device__ __forceinline__ void rotate_chunk(const _Float16* __restrict__ src, i
     }
     floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);
     U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, tl, U, 0, 0, 0);
+    bool ok = true;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) out[i] = (_Float16)(U[i] * 0.25f);
+    for (int i = 0; i < 4; ++i) {
+        out[i] = (_Float16)(U[i] * 0.25f);
+        ok = ok && __builtin_fabsf(U[i]) <= 4.0f * 65504.0f;  // (false for NaN as well)
+    }
+    return ok;
 }
 
 // Operand order of the streaming kernel.  The 16x16x32 MFMA of step t (0..7) takes from lane
@@ -52,14 +59,14 @@ __device__ __forceinline__ void rotate_chunk(const _Float16* __restrict__ src, i
 // vector registers; with the full 512 the compiler parks their results in accumulator registers and copies
 // every one of them out)
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void rotate_frag_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx, int MP,
-                                                          _Float16* __restrict__ Xt, float* __restrict__ S) {
+                                                          _Float16* __restrict__ Xt, float* __restrict__ S, uint32_t* __restrict__ flags) {
     const int64_t KB = K / kBlock;
     const int lane = lane_id();
     const int64_t chunk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // m * KB + b over MP rows
     if (chunk >= (int64_t)MP * KB) return;
     const int64_t m = chunk / KB, b = chunk - m * KB;
     _Float16 r[4] = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
-    if (m < M) rotate_chunk(X + m * ldx + b * kBlock, lane, r);
+    if (m < M && !rotate_chunk(X + m * ldx + b * kBlock, lane, r) && flags != nullptr) atomicOr(flags, kFlagActRange);
     float s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
 #pragma unroll
     for (int k = 1; k < 64; k <<= 1) s += xor_lane_f32(s, k);
@@ -81,7 +88,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
 // Operand order of the tiled kernel: rows stay rows; inside every group of 16 channels, slot s moves
 // to position 2 (s & 7) + (s >> 3), the order in which the tile loader's unpack emits the weights.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void rotate_rowmajor_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx,
-                                                              _Float16* __restrict__ Xt, uint32_t* __restrict__ zero_words, int n_zero) {
+                                                              _Float16* __restrict__ Xt, uint32_t* __restrict__ zero_words, int n_zero, uint32_t* __restrict__ flags) {
     const int64_t KB = K / kBlock;
     const int lane = lane_id();
     // the split-K flags of the contraction that follows start from zero
@@ -91,7 +98,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
     if (chunk >= M * KB) return;
     const int64_t m = chunk / KB, b = chunk - m * KB;
     _Float16 r[4];
-    rotate_chunk(X + m * ldx + b * kBlock, lane, r);
+    if (!rotate_chunk(X + m * ldx + b * kBlock, lane, r) && flags != nullptr) atomicOr(flags, kFlagActRange);
     _Float16* dst = Xt + m * K + b * kBlock;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -100,15 +107,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
     }
 }
 
-int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, hipStream_t stream) {
+int launch_rotate_frag(const _Float16* X, int64_t M, int64_t K, int64_t ldx, int MP, _Float16* Xt, float* S, uint32_t* flags, hipStream_t stream) {
     const int64_t chunks = (int64_t)MP * (K / kBlock);
-    hipLaunchKernelGGL(rotate_frag_kernel, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, stream, X, M, K, ldx, MP, Xt, S);
+    hipLaunchKernelGGL(rotate_frag_kernel, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, stream, X, M, K, ldx, MP, Xt, S, flags);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, uint32_t* zero_words, int n_zero, hipStream_t stream) {
+int launch_rotate_rowmajor(const _Float16* X, int64_t M, int64_t K, int64_t ldx, _Float16* Xt, uint32_t* zero_words, int n_zero, uint32_t* flags,
+                           hipStream_t stream) {
     const int64_t chunks = M * (K / kBlock);
-    hipLaunchKernelGGL(rotate_rowmajor_kernel, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, stream, X, M, K, ldx, Xt, zero_words, n_zero);
+    hipLaunchKernelGGL(rotate_rowmajor_kernel, dim3((unsigned)((chunks + 3) / 4)), dim3(256), 0, stream, X, M, K, ldx, Xt, zero_words, n_zero, flags);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

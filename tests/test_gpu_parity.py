@@ -455,6 +455,77 @@ def test_matmul_activation_magnitudes(gpu, ref, scale):
         assert rel_rows(got, want) <= MATMUL_TOL
 
 
+@pytest.mark.parametrize("M", [1, 3, 8, 16, 40])  # in-kernel rotation, rotation launch + streaming kernel, tiled path
+def test_matmul_activation_range_edge_and_flag(gpu, ref, M):
+    """The stated activation domain (max|x| <= 16376 and |H x| <= 65504 per 256-channel chunk): at
+    its edge the product is finite and matches the oracle with the flag clear; beyond it the library
+    says so through ITQ3S_FLAG_ACT_RANGE instead of handing back Inf/NaN silently."""
+    torch, binding = gpu
+    N, K = 96, 1024
+    codes, scales = random_packed(N, K, "range")
+    cd, sd = to_dev(torch, codes.view(np.int32)), to_dev(torch, scales.view(np.int32))
+    base = synth.activations(M, K, "range", M)
+
+    def run(X):
+        flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+        Y = binding.itq3s_matmul(cd, sd, N, K, to_dev(torch, X), status_flags=flags).cpu().numpy()
+        return Y, int(flags.item())
+
+    # (a) sixteen neighbouring channels (one row of the chunk seen as 16 x 16) at the largest allowed
+    # magnitude: the intermediate is exactly 65504
+    X = base.copy()
+    X[:, 288:304] = np.float16(16376.0)
+    X[M - 1, 768:784] = np.float16(-16376.0)
+    Y, f = run(X)
+    assert f == 0 and np.isfinite(Y).all()
+    assert rel_rows(Y, ref.matmul(codes, scales, N, K, X)) <= MATMUL_TOL
+    # (b) a whole chunk of +4094: the first rotated value is exactly 65504, the others 0
+    X = base.copy()
+    X[0, 256:512] = np.float16(4094.0)
+    Y, f = run(X)
+    assert f == 0 and np.isfinite(Y).all()
+    assert rel_rows(Y, ref.matmul(codes, scales, N, K, X)) <= MATMUL_TOL
+    # (c) the intermediate overflows (16 * 16400 / 4 rounds to infinity in fp16)
+    X = base.copy()
+    X[M - 1, 16:32] = np.float16(16400.0)
+    Y, f = run(X)
+    assert f & binding.FLAG_ACT_RANGE
+    # (d) the rotated value overflows (256 * 4100 / 16 > 65504), the intermediate does not
+    X = base.copy()
+    X[0, 512:768] = np.float16(4100.0)
+    Y, f = run(X)
+    assert f & binding.FLAG_ACT_RANGE
+    # rows that stay inside the domain are unaffected by a row that does not
+    if M > 1:
+        want = ref.matmul(codes, scales, N, K, X)
+        assert rel_rows(Y[1:], want[1:]) <= MATMUL_TOL
+
+
+def test_matmul_grouped_tiled_path_splits_by_shape_only(gpu, ref):
+    """M > 16 with one tensor above 128 output tiles (never split) and one far below (split over K)
+    in the same group: each gets exactly what a single call gives it (bit for bit), whatever the
+    other tensors are, and a workspace that is too small for the tensor that splits is refused."""
+    torch, binding = gpu
+    K, M = 2048, 300
+    Ns = [11008, 600]  # 3 x 43 = 129 tiles; 3 x 3 = 9 tiles
+    packed = [random_packed(N, K, "grp-split", i) for i, N in enumerate(Ns)]
+    dev = [(to_dev(torch, c.view(np.int32)), to_dev(torch, s.view(np.int32)), N) for (c, s), N in zip(packed, Ns)]
+    X = synth.activations(M, K, "grp-split")
+    Xd = to_dev(torch, X)
+    need = [binding.itq3s_matmul_workspace_bytes(M, N, K) for N in Ns]
+    assert need[1] > need[0]  # the small tensor asks for room for its shares
+    outs = binding.itq3s_matmul_grouped(dev, K, Xd)
+    singles = [binding.itq3s_matmul(c, s, N, K, Xd) for c, s, N in dev]
+    for o, single, (c, s), N in zip(outs, singles, packed, Ns):
+        assert torch.equal(o, single)
+        for n0, n1 in [(0, 24), (N - 24, N)]:
+            want = ref.matmul(c, s, N, K, X, rows=(n0, n1))[:, n0:n1]
+            assert rel_rows(o.cpu().numpy()[:, n0:n1], want) <= MATMUL_TOL
+    small = torch.empty(need[0], dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.Itq3sError, match="workspace"):
+        binding.itq3s_matmul_grouped(dev, K, Xd, workspace=small)
+
+
 def test_matmul_workspace_shared_by_back_to_back_calls(gpu, ref):
     """One workspace, calls of different shapes and paths enqueued back to back on one stream with no
     host synchronisation in between: each result equals the one computed alone."""
