@@ -5,25 +5,28 @@ A step is one decode pass (M = 1) over every weight tensor of a transformer-shap
 order of the layer's data flow: q, k, v (same input) -> o -> gate, up (same input) -> down.  Tensors
 that read the same activations go into one itq3s_matmul_grouped call (one launch: activation
 rotation + streaming contraction + epilogue); `--ungrouped` issues one itq3s_matmul per tensor.
-All packed weights are resident in HBM.  The default workload is the Llama-7B-shaped configuration
-(32 layers x {4 x 4096x4096, 2 x 11008x4096, 1 x 4096x11008}, 2.5 GB packed, so that no tensor is
-re-read from a cache); `--workload llama70b_decode` runs the 80-layer 70B-shaped stream (26.7 GB),
-which the default run also times as an extra leg (fp16 outputs).  Weights are synthetic (Student-t, see
-paper_2603_27914_amd/synth.py), generated on the device and packed by itq3s_quantize, which is
-timed as well.
+The default workload is the full 70B-shaped stream (80 layers, 560 tensors, 26.74 GB of packed
+weights resident in HBM: no tensor is re-read from a cache); `--workload llama7b_decode` runs the
+7B-shaped stack (32 layers, 2.5 GB), which the default run also times as an extra leg.  Weights are
+synthetic (Student-t, see paper_2603_27914_amd/synth.py), generated on the device and packed by
+itq3s_quantize, which is timed as well.
 
-Prints ONE JSON line.  `value` = packed-weight bytes streamed per second over the whole step
-(wall clock over the replayed graph, launch gaps included).  `roofline` prices the streaming
-contraction kernel alone: algorithmic bytes of a call over the kernel's own duration, which
+Prints ONE JSON line.  `value` = packed-weight bytes streamed per second over the whole step (wall
+clock over the replayed graph, launch gaps included).  `roofline` prices the streaming contraction
+kernel alone: algorithmic bytes of a call over the kernel's own duration, which
 itq3s_matmul_grouped_timed reads from HIP events attached to the kernel's dispatch, averaged over
 every call of the step (three more passes through the step, the middle reading of each call: the
-same quantity rocprofv3 --kernel-trace --stats lists as the kernel's average duration).
+same quantity rocprofv3 --kernel-trace --stats lists as the kernel's average duration).  The other
+configurations of the metric (single 2048 x 2048 GEMV, 7B and 70B shapes one by one at several M, the
+prefill GEMM at M = 512 and 2048 against the fp16 matrix-core peak) are extra legs of the same line.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -33,17 +36,6 @@ sys.path.insert(0, ROOT)
 FP64_VECTOR_PEAK_TFLOPS = 78.6
 HBM_PEAK_GBPS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2516.6  # 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
-
-# HBM traffic of the streaming kernel per launch, averaged over the step's launches, from two
-# rocprofv3 --pmc passes over this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
-# counter shows for copy_leg's 1 GiB copy; the summaries and the commands are under profiles/.
-MEASURED_TRAFFIC = {
-    # per launch of the grouped step: fetched (19417.6 + 6570.9 + 34898.1 + 17594.1) / 4 KiB, written
-    # (48 + 16 + 86 + 16) / 4 KiB, against 19,823,488 algorithmic bytes: 1.6 % of re-reads (the
-    # activations, read by every workgroup, and stand-in loads)
-    "llama7b_decode": {"bytes_per_launch": 20133555, "fetch_bytes": 20091059, "write_bytes": 42496,
-                       "source": "profiles/gemv_quantize_llama7b_decode.hbm_traffic.txt"},
-}
 
 WORKLOADS = {
     # name: (layers, stages of one layer in paper_2603_27914_amd.synth, M)
@@ -65,10 +57,11 @@ def student_t_weights(torch, gen, N, K):
     return W
 
 
-def activations(torch, gen, M, K):
+def activations(torch, gen, M, K, outliers=True):
     X = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.float32)
-    cols = torch.randperm(K, generator=gen, device="cuda")[: int(round(0.005 * K))]
-    X[:, cols] *= 10.0
+    if outliers:
+        cols = torch.randperm(K, generator=gen, device="cuda")[: int(round(0.005 * K))]
+        X[:, cols] *= 10.0
     return X.to(torch.float16)
 
 
@@ -80,17 +73,72 @@ def alg_bytes(N, K, M, y_bytes=4):
     return packed_bytes(N, K) + M * K * 2 + M * N * y_bytes
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the streaming kernel from the committed rocprofv3 --pmc summary of
+    this workload (FETCH_SIZE and WRITE_SIZE passes, scaled by the calibration copy), or None."""
+    path = os.path.join(ROOT, "profiles", "gemv_%s.hbm_traffic.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    tot = {"FETCH_SIZE": [0.0, 0], "WRITE_SIZE": [0.0, 0]}
+    for line in open(path):
+        m = re.match(r"\s*gemv_kernel\S*.*?\s(\d+)\s+(FETCH_SIZE|WRITE_SIZE)\s+(\d+)\s+([\d.]+)\s+([\d.]+)\s*$", line)
+        if m:
+            calls, scaled = int(m.group(3)), float(m.group(5))
+            tot[m.group(2)][0] += calls * scaled
+            tot[m.group(2)][1] += calls
+    if not tot["FETCH_SIZE"][1] or not tot["WRITE_SIZE"][1]:
+        return None
+    fetch = tot["FETCH_SIZE"][0] / tot["FETCH_SIZE"][1] * 1024.0
+    write = tot["WRITE_SIZE"][0] / tot["WRITE_SIZE"][1] * 1024.0
+    return {"bytes_per_launch": int(fetch + write), "fetch_bytes": int(fetch), "write_bytes": int(write), "source": os.path.relpath(path, ROOT)}
+
+
+def build_stack(torch, binding, gen, stages, layers, flags=None):
+    """Generate and pack every tensor of `layers` layers.  -> (tensors, quantize ms, quantize bytes);
+    tensors = [(N, K, codes, scales, layer, stage, name)]."""
+    tensors, q_ms, q_bytes = [], 0.0, 0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for li in range(layers):
+        for si, stage in enumerate(stages):
+            for name, N, K in stage:
+                W = student_t_weights(torch, gen, N, K)
+                codes, scales = binding.alloc_packed(N, K)
+                ev0.record()
+                binding.itq3s_quantize(W, codes, scales, status_flags=flags)
+                ev1.record()
+                ev1.synchronize()
+                q_ms += ev0.elapsed_time(ev1)
+                q_bytes += N * K * 4 + packed_bytes(N, K)
+                tensors.append((N, K, codes, scales, li, si, name))
+                del W
+    return tensors, q_ms, q_bytes
+
+
+def step_calls(tensors, stages, layers, ys, grouped=True):
+    """The library calls of a step, in order: one per stage of every layer (the tensors of a stage read
+    the same activations: one grouped call), or one per tensor."""
+    calls = []  # (K, [(codes, scales, N)], [Y])
+    for li in range(layers):
+        for si in range(len(stages)):
+            group = [t for t in tensors if t[4] == li and t[5] == si]
+            if grouped:
+                calls.append((group[0][1], [(c, s, N) for N, K, c, s, *_ in group], [ys[t[6]] for t in group]))
+            else:
+                calls.extend((K, [(c, s, N)], [ys[name]]) for N, K, c, s, _, _, name in group)
+    return calls
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama7b_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="llama70b_decode", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = the workload's own)")
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
     ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
     ap.add_argument("--prefill-m", default="512,2048", help="activation row counts of the prefill leg")
-    ap.add_argument("--legs", default="per_shape,read_floor,stream70b,prefill,dequantize,ablation,copy,cpu", help="comma list of the extra legs to run")
+    ap.add_argument("--legs", default="single,per_shape,stream7b,read_floor,prefill,dequantize,ablation,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -116,22 +164,7 @@ def main():
 
     # ------------------------------------------------------------------ build the resident weights
     flags = torch.zeros(1, dtype=torch.int32, device="cuda")
-    tensors = []  # (N, K, codes, scales, layer index, stage index, name)
-    q_ms, q_bytes = 0.0, 0
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for li in range(layers):
-        for si, stage in enumerate(stages):
-            for name, N, K in stage:
-                W = student_t_weights(torch, gen, N, K)
-                codes, scales = binding.alloc_packed(N, K)
-                ev0.record()
-                binding.itq3s_quantize(W, codes, scales, status_flags=flags)
-                ev1.record()
-                ev1.synchronize()
-                q_ms += ev0.elapsed_time(ev1)
-                q_bytes += N * K * 4 + packed_bytes(N, K)
-                tensors.append((N, K, codes, scales, li, si, name))
-                del W
+    tensors, q_ms, q_bytes = build_stack(torch, binding, gen, stages, layers, flags)
     assert int(flags.item()) == 0, "quantizer raised data flags on synthetic weights"
     xs = {}
     for stage in stages:
@@ -140,21 +173,11 @@ def main():
             xs[K] = activations(torch, gen, M, K)
     ys = {name: torch.empty((M, N), dtype=torch.float32, device="cuda") for stage in stages for name, N, K in stage}
     ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for stage in stages for _, N, K in stage), dtype=torch.uint8, device="cuda")
-
-    # the library calls of a step, in order: one per stage of every layer (the tensors of a stage read
-    # the same activations: one grouped call), or one per tensor with --ungrouped
-    calls = []  # (K, [(codes, scales, N)], [Y])
-    for li in range(layers):
-        for si in range(len(stages)):
-            group = [t for t in tensors if t[4] == li and t[5] == si]
-            if grouped:
-                calls.append((group[0][1], [(c, s, N) for N, K, c, s, *_ in group], [ys[t[6]] for t in group]))
-            else:
-                calls.extend((K, [(c, s, N)], [ys[name]]) for N, K, c, s, _, _, name in group)
+    calls = step_calls(tensors, stages, layers, ys, grouped)
 
     def step():
         for K, wts, outs in calls:
-            binding.itq3s_matmul_grouped(wts, K, xs[K], outs=outs, workspace=ws)
+            binding.itq3s_matmul_grouped(wts, K, xs[K], outs=outs, workspace=ws, status_flags=flags)
 
     # ------------------------------------------------------------------ timed region
     # The step is captured once into a HIP graph and replayed, so that the timed region measures
@@ -167,6 +190,7 @@ def main():
     for _ in range(args.warmup):
         graph.replay()
     torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
     for _ in range(args.steps):
@@ -175,6 +199,7 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = ev0.elapsed_time(ev1)
+    assert int(flags.item()) == 0, "a matmul raised data flags on synthetic inputs"
     ms_per_step = wall_ms / args.steps
     step_packed = sum(packed_bytes(N, K) for N, K, *_ in tensors)
     step_alg = sum(alg_bytes(N, K, M) for N, K, *_ in tensors)
@@ -197,9 +222,11 @@ def main():
     for (K, Ns), v in kern_ms.items():
         v = sorted(v)
         nbytes = sum(alg_bytes(N, K, M) for N in Ns)
-        per_kernel.append({"K": K, "N": list(Ns), "launches": len(v), "us_mean": round(1e3 * sum(v) / len(v), 3), "us_median": round(1e3 * v[len(v) // 2], 3),
-                           "us_min": round(1e3 * v[0], 3), "alg_bytes": nbytes, "GBps_mean": round(nbytes / (sum(v) / len(v) * 1e-3) / 1e9, 1)})
-    measured = MEASURED_TRAFFIC.get(args.workload) if layers == WORKLOADS[args.workload][0] and grouped else None
+        mean = sum(v) / len(v)
+        per_kernel.append({"K": K, "N": list(Ns), "launches": len(v), "us_mean": round(1e3 * mean, 3), "us_median": round(1e3 * v[len(v) // 2], 3),
+                           "us_min": round(1e3 * v[0], 3), "alg_bytes": nbytes, "GBps_mean": round(nbytes / (mean * 1e-3) / 1e9, 1),
+                           "frac": round(nbytes / (mean * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
+    measured = measured_traffic(args.workload) if layers == WORKLOADS[args.workload][0] and grouped else None
 
     out = {
         "metric": "ITQ3_S GEMV effective HBM GB/s on packed-weight bytes @M=1",
@@ -222,7 +249,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "gemv_kernel (itq3s_matmul / itq3s_matmul_grouped, M<=16 path)",
+            "kernel": "gemv_kernel (itq3s_matmul / itq3s_matmul_grouped, M<=4 path)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
@@ -239,22 +266,29 @@ def main():
     }
 
     legs = [] if args.no_extras else [x for x in args.legs.split(",") if x]
+    if "single" in legs:
+        out["single_gemv"] = single_leg(torch, binding, gen)
     if "per_shape" in legs:
-        out["per_shape"] = per_shape_leg(torch, binding, tensors, gen)
-    if "prefill" in legs:
-        out["prefill"] = prefill_leg(torch, binding, synth, gen, [int(m) for m in args.prefill_m.split(",")])
-    if "dequantize" in legs:
-        out["dequantize"] = dequantize_leg(torch, binding, tensors)
-    if "ablation" in legs:
-        out["block_size_ablation"] = ablation_leg(torch, binding, gen)
-    if "stream70b" in legs and args.workload != "llama70b_decode":
-        out["stream70b"] = stream70b_leg(torch, binding, synth, gen)
+        out["per_shape"] = per_shape_leg(torch, binding, tensors, gen, (1, 4, 16), torch.float16)
     if "read_floor" in legs:
         out["read_floor"] = read_floor_leg(torch, binding, tensors)
-    if "copy" in legs:
-        out["copy_ceiling"] = copy_leg(torch)
+    if "dequantize" in legs:
+        out["dequantize"] = dequantize_leg(torch, binding, tensors)
     if "cpu" in legs:
         out["cpu_baseline"] = cpu_baseline_leg(torch, binding, tensors, xs, M)
+    if "stream7b" in legs and args.workload != "llama7b_decode":
+        out["stream7b"] = stream7b_leg(torch, binding, synth, gen)
+    if "prefill" in legs:
+        out["prefill"] = prefill_leg(torch, binding, synth, gen, [int(m) for m in args.prefill_m.split(",")])
+        best = max((r for r in out["prefill"] if r["M"] == max(x["M"] for x in out["prefill"])), key=lambda r: r["kernel_TFLOPs"])
+        out["roofline_gemm"] = {"bound": "mfma", "kernel": "gemm_kernel (itq3s_matmul, M>16 path)", "achieved": best["kernel_TFLOPs"], "peak": MFMA_F16_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": round(best["kernel_TFLOPs"] / MFMA_F16_PEAK_TFLOPS, 4),
+                                "workload": "X fp16 [%d, %d] x ITQ3_S W %dx%d, fp16 out" % (best["M"], best["K"], best["N"], best["K"]),
+                                "whole_call_TFLOPs": best["TFLOPs"], "whole_call_frac": best["frac_of_mfma_peak"]}
+    if "ablation" in legs:
+        out["block_size_ablation"] = ablation_leg(torch, binding, gen)
+    if "copy" in legs:
+        out["copy_ceiling"] = copy_leg(torch)
     print(json.dumps(out))
 
 
@@ -290,10 +324,33 @@ def graph_time(torch, fn, n_calls, reps=10):
     return e0.elapsed_time(e1) / (reps * n_calls)
 
 
-def per_shape_leg(torch, binding, tensors, gen):
-    """Each shape on its own for M = 1 and M = 8, as a replayed graph: cycling through all resident
-    copies of that shape (weights come from HBM), and on one copy only (weights stay in the 256 MB
-    last-level cache; labelled as such)."""
+def single_leg(torch, binding, gen, N=2048, K=2048, copies=256):
+    """The single 2048 x 2048 GEMV (M = 1, fp32 out, no activation outliers): latency of one call, as a
+    replayed graph cycling through `copies` packed copies (420 MB: weights come from HBM) and on one
+    copy (weights stay in the last-level cache).  1.64 MB is 0.2 us of traffic at peak, far below
+    the cost of any launch: this configuration shows latency, not bandwidth."""
+    W = student_t_weights(torch, gen, N, K)
+    first = binding.itq3s_quantize(W)
+    packed = [first] + [(first[0].clone(), first[1].clone()) for _ in range(copies - 1)]
+    del W
+    X = activations(torch, gen, 1, K, outliers=False)
+    Y = torch.empty((1, N), dtype=torch.float32, device="cuda")
+    ws = torch.empty(binding.itq3s_matmul_workspace_bytes(1, N, K), dtype=torch.uint8, device="cuda")
+
+    def run(which):
+        for c, s in which:
+            binding.itq3s_matmul(c, s, N, K, X, out=Y, workspace=ws)
+
+    ms = graph_time(torch, lambda: run(packed), copies)
+    ms_hot = graph_time(torch, lambda: run(packed[:1] * 32), 32)
+    return {"N": N, "K": K, "M": 1, "us": round(ms * 1e3, 2), "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "copies": copies, "us_cache_resident": round(ms_hot * 1e3, 2)}
+
+
+def per_shape_leg(torch, binding, tensors, gen, Ms, out_dtype):
+    """Each tensor shape of the stack on its own, one call per launch, for several M, as a replayed
+    graph cycling through the resident copies of that shape (at most 24 of them, at least 0.5 GB:
+    weights come from HBM)."""
     res = []
     shapes = []
     for t in tensors:
@@ -301,20 +358,42 @@ def per_shape_leg(torch, binding, tensors, gen):
             shapes.append((t[0], t[1]))
     for N, K in shapes:
         same = [t for t in tensors if (t[0], t[1]) == (N, K)]
-        for M in (1, 8):
+        same = same[: max(2, min(len(same), 24, int(2e9 // packed_bytes(N, K)) + 1))]
+        for M in Ms:
             X = activations(torch, gen, M, K)
-            Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+            Y = torch.empty((M, N), dtype=out_dtype, device="cuda")
             ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
 
-            def run(which):
-                for N_, K_, codes, scales, *_ in which:
+            def run():
+                for N_, K_, codes, scales, *_ in same:
                     binding.itq3s_matmul(codes, scales, N_, K_, X, out=Y, workspace=ws)
 
-            ms = graph_time(torch, lambda: run(same), len(same))
-            ms_hot = graph_time(torch, lambda: run(same[:1] * 16), 16)
-            res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 2), "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1),
-                        "copies": len(same), "us_cache_resident": round(ms_hot * 1e3, 2)})
+            ms = graph_time(torch, run, len(same))
+            res.append({"N": N, "K": K, "M": M, "out": str(out_dtype).replace("torch.", ""), "us": round(ms * 1e3, 2),
+                        "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                        "copies": len(same)})
     return res
+
+
+def stream7b_leg(torch, binding, synth, gen):
+    """The 7B-shaped decode stack (32 layers, 2.53 GB packed, fp32 out) as a replayed graph of grouped
+    calls, and its shapes one by one at M = 1 and 8."""
+    stages = synth.LLAMA7B_STAGES
+    tensors, _, _ = build_stack(torch, binding, gen, stages, 32)
+    xs = {K: activations(torch, gen, 1, K) for K in sorted({st[0][2] for st in stages})}
+    ys = {name: torch.empty((1, N), dtype=torch.float32, device="cuda") for st in stages for name, N, K in st}
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    calls = step_calls(tensors, stages, 32, ys)
+    nbytes = sum(packed_bytes(t[0], t[1]) for t in tensors)
+
+    def step():
+        for K, wts, outs in calls:
+            binding.itq3s_matmul_grouped(wts, K, xs[K], outs=outs, workspace=ws)
+
+    ms = graph_time(torch, step, 1, reps=20)
+    return {"workload": "llama7b_decode shapes, 32 layers, M=1, fp32 out, %d grouped calls, %.2f GB packed" % (len(calls), nbytes / 1e9),
+            "ms_per_step": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "per_shape": per_shape_leg(torch, binding, tensors, gen, (1, 8), torch.float32)}
 
 
 def prefill_leg(torch, binding, synth, gen, m_list=(512, 2048)):
@@ -332,13 +411,15 @@ def prefill_leg(torch, binding, synth, gen, m_list=(512, 2048)):
             ws = torch.empty(binding.itq3s_matmul_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
             ms = time_calls(torch, lambda: binding.itq3s_matmul(codes, scales, N, K, X, out=Y, workspace=ws), 20)
             tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-            _, kms = binding.itq3s_matmul_timed(codes, scales, N, K, X, out=Y, workspace=ws)
+            kms = sorted(binding.itq3s_matmul_timed(codes, scales, N, K, X, out=Y, workspace=ws)[1] for _ in range(3))[1]
             # the paper's placement of the transform (inside the weight tile loader), for comparison
             binding.itq3s_matmul_weight_side(codes, scales, N, K, X, out=Y)
-            _, wms = binding.itq3s_matmul_weight_side(codes, scales, N, K, X, out=Y, timed=True)
+            wms = sorted(binding.itq3s_matmul_weight_side_timed(codes, scales, N, K, X, out=Y)[1] for _ in range(3))[1]
             res.append({"N": N, "K": K, "M": M, "us": round(ms * 1e3, 1), "TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
                         "kernel_us": round(kms * 1e3, 1), "kernel_TFLOPs": round(2.0 * M * N * K / (kms * 1e-3) / 1e12, 1),
-                        "weight_side_kernel_us": round(wms * 1e3, 1), "weight_side_TFLOPs": round(2.0 * M * N * K / (wms * 1e-3) / 1e12, 1)})
+                        "kernel_frac_of_mfma_peak": round(2.0 * M * N * K / (kms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                        "weight_side_kernel_us": round(wms * 1e3, 1), "weight_side_TFLOPs": round(2.0 * M * N * K / (wms * 1e-3) / 1e12, 1),
+                        "weight_side_overhead_pct": round(100.0 * (wms / kms - 1.0), 1)})
     return res
 
 
@@ -392,35 +473,6 @@ def ablation_leg(torch, binding, gen, N=8192, K=8192, copies=3):
     return {"N": N, "K": K, "dtype": "f64", "bound": "alu", "sizes": res}
 
 
-def stream70b_leg(torch, binding, synth, gen, n_layers=80):
-    """The full 70B-shaped decode stream (M = 1, fp16 out): 80 layers, 26.7 GB of packed weights
-    resident in HBM, one grouped call per stage, replayed graph."""
-    M = 1
-    stages = synth.LLAMA70B_STAGES
-    calls, nbytes = [], 0
-    xs = {K: activations(torch, gen, M, K) for K in sorted({st[0][2] for st in stages})}
-    ys = {name: torch.empty((M, N), dtype=torch.float16, device="cuda") for st in stages for name, N, K in st}
-    ws = torch.empty(max(binding.itq3s_matmul_workspace_bytes(M, N, K) for st in stages for _, N, K in st), dtype=torch.uint8, device="cuda")
-    for li in range(n_layers):
-        for st in stages:
-            wts = []
-            for name, N, K in st:
-                W = student_t_weights(torch, gen, N, K)
-                codes, scales = binding.itq3s_quantize(W)
-                del W
-                wts.append((codes, scales, N))
-                nbytes += packed_bytes(N, K)
-            calls.append((st[0][2], wts, [ys[name] for name, _, _ in st]))
-
-    def step():
-        for K, wts, outs in calls:
-            binding.itq3s_matmul_grouped(wts, K, xs[K], outs=outs, workspace=ws)
-
-    ms = graph_time(torch, step, 1, reps=10)
-    return {"workload": "llama70b_decode shapes, %d of 80 layers, M=1, fp16 out, %d grouped calls, %.2f GB packed" % (n_layers, len(calls), nbytes / 1e9),
-            "ms_per_step": round(ms, 4), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
-
-
 def read_floor_leg(torch, binding, tensors):
     """A plain read of the packed code arrays of every tensor shape of the step (the resident copies in
     turn, replayed graph): what a launch costs that only moves the bytes."""
@@ -432,6 +484,7 @@ def read_floor_leg(torch, binding, tensors):
             shapes.append((t[0], t[1]))
     for N, K in shapes:
         same = [t for t in tensors if (t[0], t[1]) == (N, K)]
+        same = same[: max(2, min(len(same), 24))]
 
         def run():
             for t in same:
@@ -454,30 +507,52 @@ def copy_leg(torch):
 
 
 def cpu_baseline_leg(torch, binding, tensors, xs, M):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: the M = 1 matmuls of
-    the first layers' tensors, single thread.  Also checks the GPU result of those calls against it."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the M = 1 matmuls of the
+    first layers' tensors -- once on one core, once with the output rows of every tensor dealt to all
+    host cores this process may use (the oracle itself unchanged: each thread calls it for its own
+    range of rows).  Also checks the GPU result of those calls against it."""
     from oracle import itq3s_ref as ref
 
     ref.build()
+    ref.lib()
+    ncores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp and omp.isdigit():
+        ncores = max(1, min(ncores, int(omp)))  # the box's CPU share
     per_layer = sum(packed_bytes(t[0], t[1]) for t in tensors if t[4] == 0)
-    n_layers = max(1, min(tensors[-1][4] + 1, int(1.2e9 // per_layer)))  # about 10-20 s of single-thread work
+    n_layers = max(1, min(tensors[-1][4] + 1, int(1.1e9 // per_layer)))  # about 12 s of single-thread work
     sample = [t for t in tensors if t[4] < n_layers]
-    secs, nbytes, worst = 0.0, 0, 0.0
-    for N, K, codes, scales, *_ in sample:
-        hc, hs = codes.cpu().numpy().view(np.uint32), scales.cpu().numpy().view(np.uint32)
-        X = xs[K].cpu().numpy()
-        t0 = time.perf_counter()
-        Yr = ref.matmul(hc, hs, N, K, X)
-        secs += time.perf_counter() - t0
-        nbytes += packed_bytes(N, K)
+    host = [(N, K, codes.cpu().numpy().view(np.uint32), scales.cpu().numpy().view(np.uint32), xs[K].cpu().numpy()) for N, K, codes, scales, *_ in sample]
+    nbytes = sum(packed_bytes(N, K) for N, K, *_ in host)
+
+    t0 = time.perf_counter()
+    one = [ref.matmul(hc, hs, N, K, X) for N, K, hc, hs, X in host]
+    secs1 = time.perf_counter() - t0
+
+    def rows_of(N, parts):
+        edges = [N * i // parts for i in range(parts + 1)]
+        return [(a, b) for a, b in zip(edges[:-1], edges[1:]) if b > a]
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=ncores) as pool:
+        futs = [[pool.submit(ref.matmul, hc, hs, N, K, X, r) for r in rows_of(N, ncores)] for N, K, hc, hs, X in host]
+        many = [sum(f.result() for f in fs) for fs in futs]  # each part fills its own columns, zeros elsewhere
+    secsn = time.perf_counter() - t0
+    assert all(np.array_equal(a, b) for a, b in zip(one, many)), "row-partitioned oracle differs from the single-thread oracle"
+
+    worst = 0.0
+    for (N, K, codes, scales, *_), Yr in zip(sample, one):
         Y = binding.itq3s_matmul(codes, scales, N, K, xs[K]).cpu().numpy()
         worst = max(worst, float(np.max(np.linalg.norm(Y - Yr, axis=1) / np.linalg.norm(Yr, axis=1))))
     return {
-        "value": round(nbytes / secs / 1e9, 4),
+        "value": round(nbytes / secsn / 1e9, 4),
         "unit": "GB/s",
-        "cores": 1,
+        "cores": ncores,
         "kind": "oracle",
-        "sample": "M=%d matmul of every tensor of the first %d layer(s) (%d tensors, %.1f MB packed), %.1f s of CPU time" % (M, n_layers, len(sample), nbytes / 1e6, secs),
+        "sample": "M=%d matmul of every tensor of the first %d layer(s) (%d tensors, %.1f MB packed): %.1f s on 1 core, %.1f s with the rows of each tensor dealt to %d threads"
+        % (M, n_layers, len(sample), nbytes / 1e6, secs1, secsn, ncores),
+        "single_core": {"value": round(nbytes / secs1 / 1e9, 4), "unit": "GB/s", "cores": 1, "seconds": round(secs1, 2)},
+        "host_cpus_visible": os.cpu_count(),
         "gpu_vs_oracle_max_rel_l2": worst,
     }
 

@@ -24,7 +24,7 @@
 // its private 512 M bytes of LDS in operand order, and multiplies.  No wavefront waits for another
 // before the cross-wavefront sum at the end.  Every load goes through a buffer descriptor: a row
 // tile the workgroup does not have gets an empty descriptor (its loads return zeros without touching
-// memory), so the step is branch-free.  The kernel needs about 110 registers, which leaves room for
+// memory), so the step is branch-free.  The kernel needs 86 to 128 registers, which leaves room for
 // two workgroups per compute unit: one workgroup's start-up and final sum overlap the other's
 // streaming.
 #include <hip/hip_ext.h>
@@ -138,8 +138,10 @@ __device__ __forceinline__ bool rotate_to_lds(u32x2 raw, const HadamardOperand& 
 
 // kGrouped: the launch serves several tensors (a single-tensor launch skips the lookup and the
 // fetch of the unused descriptors, which are on the way to the first load).
-template <int MP, int RT, bool kGrouped>
-__global__ __launch_bounds__(kGemvWaves * 64, 2) void gemv_kernel(const GemvArgs a) {
+// NBC > 0: every wavefront has exactly NBC blocks (K = 2048 NBC): the pipeline is straight-line code,
+// which the compiler fits into 57..92 registers instead of 86..126 -- a third workgroup per compute unit.
+template <int MP, int RT, bool kGrouped, int NBC>
+__global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(const GemvArgs a) {
     constexpr int W = kGemvWaves;
     extern __shared__ __align__(16) unsigned char smem[];
     const int KB = a.KB;
@@ -275,25 +277,35 @@ __global__ __launch_bounds__(kGemvWaves * 64, 2) void gemv_kernel(const GemvArgs
     // barriers keep the loads in front of the arithmetic they overlap with)
     issue(ring[0], 0);
     __builtin_amdgcn_sched_barrier(0);
-    int j = 0;
-    for (; j + 2 < nb; j += 2) {
-        issue(ring[1], j + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(ring[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(ring[0], j + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(ring[1]);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if (j + 2 == nb) {
-        issue(ring[1], j + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(ring[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(ring[1]);
-    } else if (j + 1 == nb) {
-        compute(ring[0]);
+    if constexpr (NBC > 0) {
+#pragma unroll
+        for (int q = 0; q < NBC; ++q) {
+            if (q + 1 < NBC) issue(ring[(q + 1) & 1], q + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(ring[q & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        int j = 0;
+        for (; j + 2 < nb; j += 2) {
+            issue(ring[1], j + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(ring[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(ring[0], j + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(ring[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (j + 2 == nb) {
+            issue(ring[1], j + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(ring[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(ring[1]);
+        } else if (j + 1 == nb) {
+            compute(ring[0]);
+        }
     }
 
     // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]; slot_out says where
@@ -323,9 +335,9 @@ __global__ __launch_bounds__(kGemvWaves * 64, 2) void gemv_kernel(const GemvArgs
     }
 }
 
-template <int MP, int RT, bool kGrouped>
+template <int MP, int RT, bool kGrouped, int NBC>
 static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
-    auto kern = gemv_kernel<MP, RT, kGrouped>;
+    auto kern = gemv_kernel<MP, RT, kGrouped, NBC>;
     const size_t lds = (size_t)kGemvWaves * MP * 512 + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
@@ -333,20 +345,27 @@ static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
-template <int MP, int RT>
+template <int MP, int RT, int NBC>
 static int launch_one(const GemvArgs& a, int grid, hipStream_t stream) {
-    if (a.t[1].v_begin != 0x7fffffff) return launch_kernel<MP, RT, true>(a, grid, stream);
-    return launch_kernel<MP, RT, false>(a, grid, stream);
+    if (a.t[1].v_begin != 0x7fffffff) return launch_kernel<MP, RT, true, NBC>(a, grid, stream);
+    return launch_kernel<MP, RT, false, NBC>(a, grid, stream);
+}
+
+template <int MP, int NBC>
+static int launch_shape(const GemvArgs& a, int grid, int rt, hipStream_t stream) {
+    switch (rt) {
+        case 1: return launch_one<MP, 1, NBC>(a, grid, stream);
+        case 2: return launch_one<MP, 2, NBC>(a, grid, stream);
+        case 3: return launch_one<MP, 3, NBC>(a, grid, stream);
+    }
+    return -2;
 }
 
 template <int MP>
-static int launch_shape(const GemvArgs& a, int grid, int rt, hipStream_t stream) {
-    switch (rt) {
-        case 1: return launch_one<MP, 1>(a, grid, stream);
-        case 2: return launch_one<MP, 2>(a, grid, stream);
-        case 3: return launch_one<MP, 3>(a, grid, stream);
-    }
-    return -2;
+static int launch_blocks(const GemvArgs& a, int grid, int rt, hipStream_t stream) {
+    if (a.KB == 8) return launch_shape<MP, 1>(a, grid, rt, stream);
+    if (a.KB == 16) return launch_shape<MP, 2>(a, grid, rt, stream);
+    return launch_shape<MP, 0>(a, grid, rt, stream);
 }
 
 int cu_count() {
@@ -381,26 +400,33 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
         t.pad_ = 0;
     }
     if (nt_total >= 0x7fffffff) return -2;
-    // Row tiles per workgroup.  A wavefront walks ceil(KB/8) blocks one after the other, and every
-    // workgroup rotates all of X for itself: with a short walk (K <= 4096) one row tile per workgroup
-    // and as many workgroups as there are tiles is fastest (measured); otherwise as many row tiles as
-    // keep one workgroup per compute unit busy, at most three (7 registers per tile and buffer).
+    // Row tiles per workgroup (every workgroup rotates all of X for itself, so more tiles per workgroup
+    // mean less of that; fewer mean more workgroups in flight).  Measured on the 7B and 70B shapes:
+    //  - K = 2048 or 4096 (a wavefront walks one or two blocks; three or four workgroups fit a compute
+    //    unit): the fewest tiles per workgroup that keep the grid within three workgroups per unit;
+    //  - otherwise: as many tiles as keep one workgroup per compute unit busy, at most three.
     const int cus = cu_count();
-    const int nb_max = (a.KB + kGemvWaves - 1) / kGemvWaves;
-    int64_t want = nb_max <= 2 ? 1 : nt_total / cus;
-    if (want < 1) want = 1;
-    if (want > kGemvMaxRT) want = kGemvMaxRT;
-    int64_t grid64 = (nt_total + want - 1) / want;
-    if (grid64 < cus && nt_total >= cus) grid64 = cus;
+    int64_t grid64;
+    if (a.KB == 8 || a.KB == 16) {
+        int64_t want = (nt_total + 3 * cus - 1) / (3 * cus);
+        if (want > kGemvMaxRT) want = kGemvMaxRT;
+        grid64 = (nt_total + want - 1) / want;
+    } else {
+        int64_t want = (nt_total + cus - 1) / cus;
+        if (want > kGemvMaxRT) want = kGemvMaxRT;
+        if (M == 2) want = 1;  // (two rows: more than one tile per workgroup would cost the second workgroup per unit)
+        grid64 = (nt_total + want - 1) / want;
+        if (grid64 < cus && nt_total >= cus) grid64 = cus;  // (workgroups then own `want` or `want - 1` tiles)
+    }
     if (grid64 > 0x7fffffff) return -2;
     const int grid = (int)grid64;
     const int rt = (int)((nt_total + grid - 1) / grid);
     a.nt_q = (int)(nt_total / grid);
     a.nt_r = (int)(nt_total % grid);
     switch (M) {
-        case 1: return launch_shape<1>(a, grid, rt, stream);
-        case 2: return launch_shape<2>(a, grid, rt, stream);
-        default: return launch_shape<4>(a, grid, rt, stream);
+        case 1: return launch_blocks<1>(a, grid, rt, stream);
+        case 2: return launch_blocks<2>(a, grid, rt, stream);
+        default: return launch_blocks<4>(a, grid, rt, stream);
     }
 }
 

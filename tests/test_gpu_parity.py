@@ -244,7 +244,7 @@ def check_elements(Y, want, codes, scales, N, K, X, out_f16=False):
 
 
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 11, 16, 17, 25, 32])  # 17..32: two passes of the streaming kernel
-@pytest.mark.parametrize("N,K", [(16, 256), (48, 512), (1000, 1024), (2048, 2048), (272, 11008), (100, 20480), (40, 36864)])
+@pytest.mark.parametrize("N,K", [(16, 256), (48, 512), (1000, 1024), (2048, 2048), (1160, 4096), (272, 11008), (100, 20480), (40, 36864)])
 def test_matmul_small_m(gpu, ref, M, N, K):
     torch, binding = gpu
     if (N, K) == (2048, 2048):
