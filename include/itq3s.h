@@ -116,6 +116,20 @@ int itq3s_matmul(const uint32_t *codes, const uint32_t *scales, int64_t N, int64
                  void *Y, int y_dtype, int64_t ldy, void *workspace, size_t workspace_bytes, uint32_t *status_flags,
                  void *stream);
 
+/* itq3s_matmul for callers that cannot hand over a workspace because they cannot allocate device
+ * memory: code that runs under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results; the scratch memory is a
+ * library-owned static device array of ITQ3S_STATIC_SCRATCH_BYTES (every GPU the library runs on
+ * holds one until the process ends), and the call allocates nothing.
+ *   - returns ITQ3S_ERR_WORKSPACE without launching anything if
+ *     itq3s_matmul_workspace_bytes(M, N, K) > ITQ3S_STATIC_SCRATCH_BYTES (M <= 4 always fits);
+ *   - all calls on one GPU share that array, which keeps the last call's contents: calls that overlap
+ *     in time on one GPU (two streams, two threads) race and must be ordered by the caller;
+ *   - the first call on a device looks up the array's address (no allocation, no synchronisation). */
+#define ITQ3S_STATIC_SCRATCH_BYTES (64u << 20)
+int itq3s_matmul_static(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
+                        int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags, void *stream);
+
 /* Several weight tensors with the same K against the same activations in ONE call: Y_t = X W_hat_t^T
  * for t = 0..count-1 (1 <= count <= ITQ3S_MAX_GROUP), e.g. the query/key/value projections of a layer,
  * or gate and up.  For M <= 16 all tensors are served by a single launch of the streaming kernel, so

@@ -24,6 +24,7 @@ EXPORTS = [
     "itq3s_roundtrip",
     "itq3s_matmul",
     "itq3s_matmul_grouped",
+    "itq3s_matmul_static",
     "itq3s_matmul_grouped_timed",
     "itq3s_matmul_timed",
     "itq3s_matmul_weight_side",
@@ -71,6 +72,8 @@ def lib():
         L.itq3s_roundtrip.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, i64, vp, vp, vp]
         L.itq3s_matmul.restype = ci
         L.itq3s_matmul.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
+        L.itq3s_matmul_static.restype = ci
+        L.itq3s_matmul_static.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul_grouped.restype = ci
         L.itq3s_matmul_grouped.argtypes = [ctypes.POINTER(Weight), ci, i64, vp, i64, i64, ci, vp, sz, vp, vp]
         L.itq3s_matmul_grouped_timed.restype = ci
@@ -300,6 +303,22 @@ def itq3s_matmul_grouped(weights, K, X, outs=None, dtype=torch.float32, workspac
     else:
         _check(lib().itq3s_matmul_grouped_timed(*args, ctypes.byref(_timed)))
     return outs
+
+
+def itq3s_matmul_static(codes, scales, N, K, X, out, status_flags=None):
+    """itq3s_matmul with the scratch in the library's static device array: nothing is allocated, so
+    `out` (float32/float16 [M, N]) must be given."""
+    _need_cuda(codes, scales, X, out, status_flags)
+    _need_packed(codes, scales, N, K, X, out, status_flags)
+    _need_flags(status_flags)
+    if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
+        raise Itq3sError("X must be float16 [M, K] with unit column stride")
+    M = X.shape[0]
+    if out.dtype not in (torch.float32, torch.float16) or out.dim() != 2 or out.stride(1) != 1 or tuple(out.shape) != (M, N):
+        raise Itq3sError("out must be float32/float16 [M, N] with unit column stride")
+    _check(lib().itq3s_matmul_static(_ptr(codes), _ptr(scales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if out.dtype == torch.float16 else F32,
+                                     out.stride(0), _ptr(status_flags), _stream()))
+    return out
 
 
 def itq3s_matmul_timed(codes, scales, N, K, X, out=None, dtype=torch.float32, workspace=None, status_flags=None):

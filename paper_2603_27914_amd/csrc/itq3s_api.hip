@@ -4,7 +4,34 @@
 #include "../../include/itq3s_bench.h"
 #include "itq3s_kernels.h"
 
+#include <atomic>
+#include <mutex>
+
+// Scratch of itq3s_matmul_static: one array per device the library runs on, held until the process
+// ends.  The name below is a host-side stand-in for the symbol; device code gets the address that
+// hipGetSymbolAddress returns for the current device (scratch_of_current_device).
+static __device__ __align__(256) unsigned char scratch[ITQ3S_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the current device (looked up once per device), or null.
+void* scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p != nullptr) return p;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -192,6 +219,16 @@ int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64
     if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
     const itq3s_weight w = {codes, scales, N, Y, ldy};
     return itq3s_matmul_grouped(&w, 1, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream);
+}
+
+int itq3s_matmul_static(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx, void* Y,
+                        int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream) {
+    if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
+    if (itq3s_matmul_workspace_bytes(M, N, K) > (size_t)ITQ3S_STATIC_SCRATCH_BYTES) return ITQ3S_ERR_WORKSPACE;
+    void* ws = scratch_of_current_device();
+    if (ws == nullptr) return ITQ3S_ERR_LAUNCH;
+    return itq3s_matmul(codes, scales, N, K, X, M, ldx, Y, y_dtype, ldy, ws, (size_t)ITQ3S_STATIC_SCRATCH_BYTES, status_flags, stream);
 }
 
 int itq3s_matmul_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx,
