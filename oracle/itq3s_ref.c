@@ -405,6 +405,182 @@ int itq3s_ref_matmul(const uint32_t *codes, const uint32_t *scales, int64_t N, i
     return itq3s_ref_matmul_rows(codes, scales, N, K, X, M, ldx, Y, ldy, 0, N);
 }
 
+/* ------------------------------------------------------------------ sub-block-scale variant (Sec. 4.1, "Block Structure") */
+
+/* The paper lists, as an option "for higher fidelity", 8 fp16 sub-block scales for 8 sub-blocks of
+ * 32 elements on top of d_k and z_k: 96 + 2 + 2 + 16 = 116 bytes per block, 3.625 bit/weight.  It
+ * gives no formula for them.  Reading taken here (PARITY UNPINNED beyond the byte budget, the
+ * reduction to the base format for sub-scales 1, and the dense definition in the tests):
+ *   - the sub-blocks are 32 consecutive coefficients of the ROTATED block w' = H w (the domain the
+ *     codes live in), sub-block j = coefficients 32j .. 32j+31;
+ *   - d_k and z_k are exactly those of the base format (Alg. 1), so the first 100 bytes keep their
+ *     meaning; the zero-point stays in units of d_k;
+ *   - s_j is the step of sub-block j relative to d_k:  s_j = T* sigma_j / d_k  with sigma_j the
+ *     deviation of the sub-block's coefficients about the BLOCK mean (population, over 32), i.e. the
+ *     Sec. 3.3 rule "scale = T* x empirical standard deviation" applied per sub-block; rounded to fp16
+ *     through fp32 like d_k, and the codes are decided against the rounded value;
+ *   - code:  q = clamp(floor((w'/d_k + z_k) / s_j + 0.5), -1, 1)  -- Def. 1 with the digit step s_j --
+ *     through the exact thresholds  w' >= (0.5 s_j - z) d  and  w' < (-0.5 s_j - z) d ; a sub-block
+ *     with s_j = 0 stores digit 0 everywhere;
+ *   - reconstruction (Prop. 1 with the digit scaled):  w_hat = H( d_k ( s_j q - z_k ) ).
+ * Sub-scale storage: one uint32 per (tile, lane) at index tile*64 + lane, lane = 16*g + r for tile
+ * row r and quarter g of the block: bits 0..15 = fp16 s_(2g), bits 16..31 = fp16 s_(2g+1)
+ * (256 bytes per tile = 16 bytes per block). */
+
+size_t itq3s_ref_subscales_bytes(int64_t N, int64_t K) { return (size_t)((N + 15) / 16) * (size_t)(K / 256) * 256u; }
+
+static double ref_pairwise_sum32(const double *v)
+{
+    double t[32];
+    memcpy(t, v, sizeof t);
+    for (int step = 1; step < 32; step <<= 1)
+        for (int i = 0; i < 32; i += 2 * step) t[i] = t[i] + t[i + step];
+    return t[0];
+}
+
+/* One block: codes (256 bytes), 8 sub-scale bit patterns; returns the scale word of the base format. */
+static uint32_t ref_quantize_block_sub(const float *w, uint8_t *codes_out, uint16_t *sub_out, uint32_t *flags)
+{
+    double a[ITQ3S_REF_BLOCK], e2[ITQ3S_REF_BLOCK];
+    int finite = 1;
+    memset(codes_out, 1, ITQ3S_REF_BLOCK);
+    for (int j = 0; j < 8; j++) sub_out[j] = 0;
+    for (int j = 0; j < ITQ3S_REF_BLOCK; j++) {
+        a[j] = (double)w[j];
+        if (!isfinite(a[j])) finite = 0;
+    }
+    if (!finite) {
+        if (flags) *flags |= REF_FLAG_NONFINITE;
+        return 0u;
+    }
+    itq3s_ref_fwht256(a);
+    for (int j = 0; j < ITQ3S_REF_BLOCK; j++) a[j] = a[j] * 0.0625;
+    double mu = ref_pairwise_sum256(a) / 256.0;
+    for (int j = 0; j < ITQ3S_REF_BLOCK; j++) {
+        double dev = a[j] - mu;
+        e2[j] = dev * dev;
+    }
+    double sigma = sqrt(ref_pairwise_sum256(e2) / 256.0);
+    double d64 = ITQ3S_REF_T_STAR * sigma;
+    if (d64 > 65504.0) {
+        d64 = 65504.0;
+        if (flags) *flags |= REF_FLAG_SCALE_SAT;
+    }
+    uint16_t dbits = ref_f32_to_f16((float)d64);
+    double d = ref_f16_to_f64(dbits);
+    if (!(d > 0.0)) return 0u;
+    double r = floor(mu / d + 0.5);
+    double z = 0.0 - r;
+    if (z > 2048.0) { z = 2048.0; if (flags) *flags |= REF_FLAG_Z_CLAMP; }
+    if (z < -2048.0) { z = -2048.0; if (flags) *flags |= REF_FLAG_Z_CLAMP; }
+    for (int j = 0; j < 8; j++) {
+        double sigma_j = sqrt(ref_pairwise_sum32(e2 + 32 * j) / 32.0);
+        double s64 = ITQ3S_REF_T_STAR * sigma_j / d;
+        if (s64 > 65504.0) {
+            s64 = 65504.0;
+            if (flags) *flags |= REF_FLAG_SCALE_SAT;
+        }
+        sub_out[j] = ref_f32_to_f16((float)s64);
+        double s = ref_f16_to_f64(sub_out[j]);
+        if (!(s > 0.0)) continue; /* digit 0 everywhere */
+        double t_hi = (0.5 * s - z) * d, t_lo = (-0.5 * s - z) * d;
+        for (int i = 32 * j; i < 32 * j + 32; i++) codes_out[i] = (uint8_t)(a[i] >= t_hi ? 2 : (a[i] < t_lo ? 0 : 1));
+    }
+    uint16_t zbits = ref_f32_to_f16((float)z);
+    return (uint32_t)dbits | ((uint32_t)zbits << 16);
+}
+
+int itq3s_ref_quantize_sub(const float *W, int64_t N, int64_t K, int64_t ldw, uint32_t *codes, uint32_t *scales, uint32_t *subs,
+                           uint32_t *flags)
+{
+    if (!W || !codes || !scales || !subs) return -1;
+    if (N <= 0 || K <= 0 || (K % 256) != 0 || ldw < K) return -2;
+    int64_t KB = K / 256, NT = (N + 15) / 16;
+    uint8_t c[ITQ3S_REF_BLOCK];
+    uint16_t sb[8];
+    for (int64_t n = 0; n < NT * 16; n++)
+        for (int64_t b = 0; b < KB; b++) {
+            uint32_t word = 0;
+            if (n < N) word = ref_quantize_block_sub(W + n * ldw + b * 256, c, sb, flags);
+            else {
+                memset(c, 1, sizeof c);
+                memset(sb, 0, sizeof sb);
+            }
+            size_t t = ref_tile_index(n, b, KB);
+            uint32_t *tile = codes + t * ITQ3S_REF_TILE_WORDS;
+            for (int e = 0; e < ITQ3S_REF_BLOCK; e++) ref_put_code(tile, (int)(n & 15), e, c[e]);
+            scales[t * 16 + (n & 15)] = word;
+            for (int g = 0; g < 4; g++) subs[t * 64 + 16 * g + (n & 15)] = (uint32_t)sb[2 * g] | ((uint32_t)sb[2 * g + 1] << 16);
+        }
+    return 0;
+}
+
+static void ref_dequantize_block_sub(const uint32_t *tile, const uint32_t *subs_tile, int r, uint32_t scale_word, double *out, uint32_t *flags)
+{
+    double d = ref_f16_to_f64((uint16_t)(scale_word & 0xffffu));
+    double z = ref_f16_to_f64((uint16_t)(scale_word >> 16));
+    double v[ITQ3S_REF_BLOCK];
+    for (int e = 0; e < ITQ3S_REF_BLOCK; e++) {
+        uint32_t c = ref_get_code(tile, r, e);
+        if (c > 2u && flags) *flags |= REF_FLAG_BAD_CODE;
+        int j = e >> 5; /* sub-block */
+        uint32_t sw = subs_tile[16 * (j >> 1) + r];
+        double s = ref_f16_to_f64((uint16_t)((j & 1) ? (sw >> 16) : (sw & 0xffffu)));
+        v[e] = s * ((double)c - 1.0) - z;
+    }
+    itq3s_ref_fwht256(v);
+    for (int e = 0; e < ITQ3S_REF_BLOCK; e++) out[e] = d * v[e] * 0.0625;
+}
+
+int itq3s_ref_dequantize_sub(const uint32_t *codes, const uint32_t *scales, const uint32_t *subs, int64_t N, int64_t K, double *W_out,
+                             int64_t ldo, uint32_t *flags)
+{
+    if (!codes || !scales || !subs || !W_out) return -1;
+    if (N <= 0 || K <= 0 || (K % 256) != 0 || ldo < K) return -2;
+    int64_t KB = K / 256;
+    for (int64_t n = 0; n < N; n++)
+        for (int64_t b = 0; b < KB; b++) {
+            size_t t = ref_tile_index(n, b, KB);
+            ref_dequantize_block_sub(codes + t * ITQ3S_REF_TILE_WORDS, subs + t * 64, (int)(n & 15), scales[t * 16 + (n & 15)],
+                                     W_out + n * ldo + b * 256, flags);
+        }
+    return 0;
+}
+
+/* Y = X W_hat^T for the sub-block variant, rows n0 <= n < n1, as itq3s_ref_matmul_rows. */
+int itq3s_ref_matmul_sub_rows(const uint32_t *codes, const uint32_t *scales, const uint32_t *subs, int64_t N, int64_t K, const uint16_t *X,
+                              int64_t M, int64_t ldx, double *Y, int64_t ldy, int64_t n0, int64_t n1)
+{
+    if (!codes || !scales || !subs || !X || !Y) return -1;
+    if (N <= 0 || K <= 0 || M <= 0 || (K % 256) != 0 || ldx < K || ldy < N || n0 < 0 || n1 > N || n0 > n1) return -2;
+    int64_t KB = K / 256;
+    double *wrow = (double *)malloc((size_t)K * sizeof(double));
+    double *xrow = (double *)malloc((size_t)M * (size_t)K * sizeof(double));
+    if (!wrow || !xrow) { free(wrow); free(xrow); return -3; }
+    for (int64_t m = 0; m < M; m++)
+        for (int64_t k = 0; k < K; k++) xrow[m * K + k] = ref_f16_to_f64(X[m * ldx + k]);
+    for (int64_t n = n0; n < n1; n++) {
+        for (int64_t b = 0; b < KB; b++) {
+            size_t t = ref_tile_index(n, b, KB);
+            ref_dequantize_block_sub(codes + t * ITQ3S_REF_TILE_WORDS, subs + t * 64, (int)(n & 15), scales[t * 16 + (n & 15)], wrow + b * 256, NULL);
+        }
+        for (int64_t m = 0; m < M; m++) {
+            double acc = 0.0;
+            const double *x = xrow + m * K;
+            for (int64_t k = 0; k < K; k++) acc += x[k] * wrow[k];
+            Y[m * ldy + n] = acc;
+        }
+    }
+    free(wrow);
+    free(xrow);
+    return 0;
+}
+
+uint32_t itq3s_ref_quantize_block_sub(const float *w, uint8_t *codes_out, uint16_t *sub_out, uint32_t *flags)
+{
+    return ref_quantize_block_sub(w, codes_out, sub_out, flags);
+}
+
 /* ------------------------------------------------------------------ small exports for the tests */
 
 /* The forward normalised transform of one block, as the quantizer sees it (w' = H w). */

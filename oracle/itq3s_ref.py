@@ -44,6 +44,13 @@ def lib():
         L.itq3s_ref_matmul.argtypes = [u32p, u32p, i64, i64, vp, i64, i64, vp, i64]
         L.itq3s_ref_matmul_rows.argtypes = [u32p, u32p, i64, i64, vp, i64, i64, vp, i64, i64, i64]
         L.itq3s_ref_roundtrip_n.argtypes = [vp, i64, i64, i64, ctypes.c_int, vp, u32p, vp, u32p]
+        L.itq3s_ref_subscales_bytes.restype = ctypes.c_size_t
+        L.itq3s_ref_subscales_bytes.argtypes = [i64, i64]
+        L.itq3s_ref_quantize_sub.argtypes = [vp, i64, i64, i64, u32p, u32p, u32p, u32p]
+        L.itq3s_ref_dequantize_sub.argtypes = [u32p, u32p, u32p, i64, i64, vp, i64, u32p]
+        L.itq3s_ref_matmul_sub_rows.argtypes = [u32p, u32p, u32p, i64, i64, vp, i64, i64, vp, i64, i64, i64]
+        L.itq3s_ref_quantize_block_sub.argtypes = [vp, vp, vp, u32p]
+        L.itq3s_ref_quantize_block_sub.restype = ctypes.c_uint32
         L.itq3s_ref_fwht256.argtypes = [vp]
         L.itq3s_ref_fwht256.restype = None
         L.itq3s_ref_forward_block.argtypes = [vp, vp]
@@ -162,3 +169,59 @@ def f16_bits_to_f64(h):
 
 def t_star():
     return float(lib().itq3s_ref_t_star())
+
+
+# ---- sub-block-scale variant (116 bytes per block)
+
+
+def subscales_words(N, K):
+    return lib().itq3s_ref_subscales_bytes(N, K) // 4
+
+
+def quantize_block_sub(w):
+    """-> (codes uint8[256], scale word, sub-scale bit patterns uint16[8], flags)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    assert w.shape == (256,)
+    codes = np.empty(256, dtype=np.uint8)
+    subs = np.zeros(8, dtype=np.uint16)
+    flags = np.zeros(1, dtype=np.uint32)
+    word = lib().itq3s_ref_quantize_block_sub(_ptr(w), _ptr(codes), _ptr(subs), _ptr(flags))
+    return codes, int(word), subs, int(flags[0])
+
+
+def quantize_sub(W):
+    """W fp32 [N, K] -> (codes uint32, scales uint32, subscales uint32, flags)."""
+    W = np.asarray(W)
+    assert W.dtype == np.float32 and W.ndim == 2 and W.strides[1] == 4
+    N, K = W.shape
+    codes = np.zeros(codes_words(N, K), dtype=np.uint32)
+    scales = np.zeros(scales_words(N, K), dtype=np.uint32)
+    subs = np.zeros(subscales_words(N, K), dtype=np.uint32)
+    flags = np.zeros(1, dtype=np.uint32)
+    _check(lib().itq3s_ref_quantize_sub(_ptr(W), N, K, W.strides[0] // 4, _ptr(codes), _ptr(scales), _ptr(subs), _ptr(flags)))
+    return codes, scales, subs, int(flags[0])
+
+
+def dequantize_sub(codes, scales, subs, N, K, return_flags=False):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    scales = np.ascontiguousarray(scales, dtype=np.uint32)
+    subs = np.ascontiguousarray(subs, dtype=np.uint32)
+    assert codes.size == codes_words(N, K) and scales.size == scales_words(N, K) and subs.size == subscales_words(N, K)
+    out = np.empty((N, K), dtype=np.float64)
+    flags = np.zeros(1, dtype=np.uint32)
+    _check(lib().itq3s_ref_dequantize_sub(_ptr(codes), _ptr(scales), _ptr(subs), N, K, _ptr(out), K, _ptr(flags)))
+    return (out, int(flags[0])) if return_flags else out
+
+
+def matmul_sub(codes, scales, subs, N, K, X, rows=None):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    scales = np.ascontiguousarray(scales, dtype=np.uint32)
+    subs = np.ascontiguousarray(subs, dtype=np.uint32)
+    X = np.ascontiguousarray(X)
+    assert X.dtype == np.float16 and X.ndim == 2 and X.shape[1] == K
+    assert codes.size == codes_words(N, K) and scales.size == scales_words(N, K) and subs.size == subscales_words(N, K)
+    M = X.shape[0]
+    Y = np.zeros((M, N), dtype=np.float64)
+    n0, n1 = (0, N) if rows is None else rows
+    _check(lib().itq3s_ref_matmul_sub_rows(_ptr(codes), _ptr(scales), _ptr(subs), N, K, _ptr(X), M, K, _ptr(Y), N, n0, n1))
+    return Y

@@ -1,10 +1,16 @@
 """Condense rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-  python -m paper_2603_27914_amd.profsum stats <..._kernel_stats.csv>
+  python profsum.py stats <..._kernel_stats.csv>
       rows of `rocprofv3 --kernel-trace --stats --output-format csv` for this library's kernels
       (and the runtime's copy kernel): calls, average / min / max duration.
 
-  python -m paper_2603_27914_amd.profsum pmc <..._counter_collection.csv> --copy-kib 1048576
+  python profsum.py gaps <..._kernel_trace.csv>
+      from the per-dispatch begin/end stamps of the same run: for every launch shape of the streaming
+      kernel, its mean duration and the mean idle time between the end of the previous dispatch and
+      its own begin (only where the previous dispatch is the streaming kernel too, i.e. inside a
+      replayed step), and the two sums per step.
+
+  python profsum.py pmc <..._counter_collection.csv> --copy-kib 1048576
       per kernel and launch shape, the mean of the collected counter (FETCH_SIZE or WRITE_SIZE, KiB
       per dispatch), the calibration factor (known KiB of bench.py's plain 1 GiB copy / what the same
       counter shows for it) and the scaled value.
@@ -13,6 +19,8 @@ import argparse
 import collections
 import csv
 import re
+
+csv.field_size_limit(1 << 30)
 
 
 def short(name):
@@ -29,6 +37,31 @@ def stats(path):
     for r in csv.DictReader(open(path)):
         if ours(r["Name"]):
             print("%-44s %7d %12.1f %10d %10d" % (short(r["Name"])[:44], int(r["Calls"]), float(r["AverageNs"]), int(r["MinNs"]), int(r["MaxNs"])))
+
+
+def gaps(path):
+    rows = []
+    for r in csv.DictReader(open(path)):
+        rows.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), short(r["Kernel_Name"]), int(r.get("Grid_Size", r.get("Grid_Size_X", 0)) or 0)))
+    rows.sort()
+    agg = collections.defaultdict(lambda: [0, 0.0, 0.0, 0])  # calls, duration, gap, gaps counted
+    prev = None
+    for st, en, name, grid in rows:
+        if "gemv_kernel" in name:
+            a = agg[(name, grid)]
+            a[0] += 1
+            a[1] += en - st
+            if prev is not None and "gemv_kernel" in prev[2] and 0 <= st - prev[1] < 20000:
+                a[2] += st - prev[1]
+                a[3] += 1
+        prev = (st, en, name, grid)
+    print("%-40s %9s %7s %12s %14s" % ("kernel", "threads", "calls", "avg_ns", "avg_gap_ns"))
+    tot_d = tot_g = 0.0
+    for (name, grid), (calls, dur, gap, ng) in sorted(agg.items()):
+        print("%-40s %9d %7d %12.1f %14.1f" % (name[:40], grid, calls, dur / calls, gap / ng if ng else float("nan")))
+        tot_d += dur / calls
+        tot_g += gap / ng if ng else 0.0
+    print("one launch of each shape: %.1f ns of kernel time + %.1f ns idle in front of them" % (tot_d, tot_g))
 
 
 def pmc(path, copy_kib):
@@ -50,12 +83,14 @@ def pmc(path, copy_kib):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("mode", choices=["stats", "pmc"])
+    ap.add_argument("mode", choices=["stats", "gaps", "pmc"])
     ap.add_argument("csv")
     ap.add_argument("--copy-kib", type=float, default=0.0, help="known KiB the calibration copy reads (= writes)")
     a = ap.parse_args()
     if a.mode == "stats":
         stats(a.csv)
+    elif a.mode == "gaps":
+        gaps(a.csv)
     else:
         pmc(a.csv, a.copy_kib)
 

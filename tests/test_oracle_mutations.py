@@ -38,6 +38,11 @@ MUTATIONS = [
     ("scale word halves swapped", "(uint32_t)dbits | ((uint32_t)zbits << 16)", "(uint32_t)zbits | ((uint32_t)dbits << 16)"),
     ("n-point round trip: normalisation of n = 128", "case 128: return 0.08838834764831843;", "case 128: return 0.0883883476483;"),
     ("n-point round trip: reconstruction forgets z", "m[j] = (double)((int)c[j] - 1) - z;", "m[j] = (double)((int)c[j] - 1);"),
+    ("sub-scales: deviation over 31", "double sigma_j = sqrt(ref_pairwise_sum32(e2 + 32 * j) / 32.0);", "double sigma_j = sqrt(ref_pairwise_sum32(e2 + 32 * j) / 31.0);"),
+    ("sub-scales: threshold ignores the sub-scale", "double t_hi = (0.5 * s - z) * d, t_lo = (-0.5 * s - z) * d;", "double t_hi = (0.5 - z) * d, t_lo = (-0.5 * s - z) * d;"),
+    ("sub-scales: zero-point scaled by the sub-scale", "v[e] = s * ((double)c - 1.0) - z;", "v[e] = s * (((double)c - 1.0) - z);"),
+    ("sub-scales: halves of the storage word swapped", "(uint32_t)sb[2 * g] | ((uint32_t)sb[2 * g + 1] << 16)", "(uint32_t)sb[2 * g + 1] | ((uint32_t)sb[2 * g] << 16)"),
+    ("sub-scales: relative to sigma instead of d", "double s64 = ITQ3S_REF_T_STAR * sigma_j / d;", "double s64 = sigma_j / sigma;"),
     ("n-point round trip: mean over n - 1", "double mu = ref_pairwise_sum_n(a, n) / (double)n;", "double mu = ref_pairwise_sum_n(a, n) / (double)(n - 1);"),
 ]
 
@@ -49,7 +54,8 @@ def run_pins_against(tmp_path, idx, old, new):
     with open(src, "w") as f:
         f.write(text.replace(old, new, 1))
     env = dict(os.environ, ITQ3S_REF_SRC=src, ITQ3S_REF_LIB=os.path.join(str(tmp_path), "libmut%d.so" % idx))
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q", "-p", "no:cacheprovider"],
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), os.path.join(ROOT, "tests", "test_oracle_sub_pins.py"),
+                        "-x", "-q", "-p", "no:cacheprovider"],
                        cwd=ROOT, env=env, capture_output=True, text=True)
     return r.returncode, r.stdout[-400:]
 
