@@ -184,6 +184,33 @@ int itq3s_matmul_weight_side(const uint32_t *codes, const uint32_t *scales, int6
 int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block_size, uint8_t *codes_out, uint32_t *scales_out,
                     float *W_hat, int64_t ldo, double *err2, uint32_t *status_flags, void *stream);
 
+/* ---- The sub-block-scale variant of the format (Sec. 4.1, "Block Structure": 8 fp16 sub-block scales
+ * for 8 sub-blocks of 32 elements, 116 bytes per block, 3.625 bit/weight).  The paper names the option
+ * and its size and gives no formula; this library's reading:
+ *   - sub-block j = rotated coefficients 32j .. 32j+31 of the block (the domain the codes live in);
+ *   - d and z are exactly those of the 100-byte format (codes and scales arrays keep their layout and
+ *     meaning; the zero-point stays in units of d);
+ *   - s_j = 0.7979 sigma_j / d, sigma_j the deviation of the sub-block's coefficients about the block
+ *     mean, rounded to fp16 through fp32 (the rule of Sec. 3.3 applied per sub-block);
+ *   - code = 1 + clamp(floor((w'/d + z) / s_j + 0.5), -1, 1)  (Def. 1 with the digit step s_j);
+ *   - w_hat = H( d (s_j q - z) )  (Prop. 1 with the scaled digit).
+ * With every s_j = 1 this is the 100-byte format.
+ *   subscales: NT*KB*64 uint32 (itq3s_subscales_bytes), 16-byte aligned; word (nt*KB + b)*64 + 16 g + r =
+ *     fp16 s_(2g) | fp16 s_(2g+1) << 16 for tile row r and quarter g of the block (0 for rows >= N).
+ * Other arguments, flags and errors as for itq3s_quantize / itq3s_dequantize / itq3s_matmul.
+ * itq3s_matmul_sub needs no workspace: it runs ceil(M/4) passes of the streaming kernel (the variant
+ * has no tiled path).  It multiplies with the sub-scales in fp16: exact for 1/16 <= s_j <= 4094 (the
+ * quantizer's values lie below 3); smaller ones lose low bits of a small contribution, larger ones
+ * are not supported. */
+size_t itq3s_subscales_bytes(int64_t N, int64_t K);
+int itq3s_quantize_sub(const float *W, int64_t N, int64_t K, int64_t ldw, uint32_t *codes, uint32_t *scales,
+                       uint32_t *subscales, uint32_t *status_flags, void *stream);
+int itq3s_dequantize_sub(const uint32_t *codes, const uint32_t *scales, const uint32_t *subscales, int64_t N, int64_t K,
+                         void *W_out, int out_dtype, int64_t ldo, uint32_t *status_flags, void *stream);
+int itq3s_matmul_sub(const uint32_t *codes, const uint32_t *scales, const uint32_t *subscales, int64_t N, int64_t K,
+                     const void *X, int64_t M, int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags,
+                     void *stream);
+
 /* Static text for a status code.  Never NULL. */
 const char *itq3s_strerror(int status);
 

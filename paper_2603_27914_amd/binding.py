@@ -25,6 +25,10 @@ EXPORTS = [
     "itq3s_matmul",
     "itq3s_matmul_grouped",
     "itq3s_matmul_static",
+    "itq3s_subscales_bytes",
+    "itq3s_quantize_sub",
+    "itq3s_dequantize_sub",
+    "itq3s_matmul_sub",
     "itq3s_matmul_grouped_timed",
     "itq3s_matmul_timed",
     "itq3s_matmul_weight_side",
@@ -72,6 +76,14 @@ def lib():
         L.itq3s_roundtrip.argtypes = [vp, i64, i64, i64, ci, vp, vp, vp, i64, vp, vp, vp]
         L.itq3s_matmul.restype = ci
         L.itq3s_matmul.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
+        L.itq3s_subscales_bytes.restype = sz
+        L.itq3s_subscales_bytes.argtypes = [i64, i64]
+        L.itq3s_quantize_sub.restype = ci
+        L.itq3s_quantize_sub.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp, vp]
+        L.itq3s_dequantize_sub.restype = ci
+        L.itq3s_dequantize_sub.argtypes = [vp, vp, vp, i64, i64, vp, ci, i64, vp, vp]
+        L.itq3s_matmul_sub.restype = ci
+        L.itq3s_matmul_sub.argtypes = [vp, vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul_static.restype = ci
         L.itq3s_matmul_static.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul_grouped.restype = ci
@@ -351,4 +363,60 @@ def itq3s_matmul(codes, scales, N, K, X, out=None, dtype=torch.float32, workspac
         _check(lib().itq3s_matmul(*args))
     else:
         _check(lib().itq3s_matmul_timed(*args, ctypes.byref(_timed)))
+    return out
+
+
+# ---- the sub-block-scale variant of the format (116 bytes per block)
+
+
+def itq3s_subscales_bytes(N, K):
+    return lib().itq3s_subscales_bytes(N, K)
+
+
+def _need_subscales(subscales, codes, N, K):
+    nbytes = itq3s_subscales_bytes(N, K)
+    if subscales.dtype != torch.int32 or not subscales.is_contiguous() or subscales.numel() * 4 < nbytes or subscales.device != codes.device:
+        raise Itq3sError("subscales must be a contiguous int32 tensor of at least %d bytes on the device of codes" % nbytes)
+
+
+def itq3s_quantize_sub(W, status_flags=None):
+    """W: float32 [N, K] device tensor -> (codes, scales, subscales) int32 device tensors."""
+    _need_cuda(W, status_flags)
+    _need_flags(status_flags)
+    if W.dtype != torch.float32 or W.dim() != 2 or W.stride(1) != 1:
+        raise Itq3sError("W must be float32 [N, K] with unit column stride")
+    N, K = W.shape
+    codes, scales = alloc_packed(N, K, W.device)
+    subscales = torch.empty(itq3s_subscales_bytes(N, K) // 4, dtype=torch.int32, device=W.device)
+    _check(lib().itq3s_quantize_sub(_ptr(W), N, K, W.stride(0), _ptr(codes), _ptr(scales), _ptr(subscales), _ptr(status_flags), _stream()))
+    return codes, scales, subscales
+
+
+def itq3s_dequantize_sub(codes, scales, subscales, N, K, dtype=torch.float32, status_flags=None):
+    _need_cuda(codes, scales, subscales, status_flags)
+    _need_packed(codes, scales, N, K, subscales, status_flags)
+    _need_subscales(subscales, codes, N, K)
+    _need_flags(status_flags)
+    if dtype not in (torch.float32, torch.float16):
+        raise Itq3sError("dtype must be float32 or float16")
+    out = torch.empty((N, K), dtype=dtype, device=codes.device)
+    _check(lib().itq3s_dequantize_sub(_ptr(codes), _ptr(scales), _ptr(subscales), N, K, _ptr(out), F16 if dtype == torch.float16 else F32, out.stride(0),
+                                      _ptr(status_flags), _stream()))
+    return out
+
+
+def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, status_flags=None):
+    """Y[M, N] = X[M, K] @ W_hat[N, K]^T from weights packed in the sub-block-scale variant."""
+    _need_cuda(codes, scales, subscales, X, status_flags)
+    _need_packed(codes, scales, N, K, subscales, X, status_flags)
+    _need_subscales(subscales, codes, N, K)
+    _need_flags(status_flags)
+    if X.dtype != torch.float16 or X.dim() != 2 or X.stride(1) != 1 or X.shape[1] != K:
+        raise Itq3sError("X must be float16 [M, K] with unit column stride")
+    if dtype not in (torch.float32, torch.float16):
+        raise Itq3sError("dtype must be float32 or float16")
+    M = X.shape[0]
+    out = torch.empty((M, N), dtype=dtype, device=X.device)
+    _check(lib().itq3s_matmul_sub(_ptr(codes), _ptr(scales), _ptr(subscales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if dtype == torch.float16 else F32,
+                                  out.stride(0), _ptr(status_flags), _stream()))
     return out

@@ -117,7 +117,7 @@ int itq3s_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* 
     if (((N + 15) / 16) * (K / 256) > 0x3fffffffLL) return ITQ3S_ERR_SHAPE;  // two workgroups per tile, 32-bit grid
     if (!aligned(W, 16) || ldw % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
-    return itq3s::launch_quantize(W, N, K, ldw, codes, scales, status_flags, static_cast<hipStream_t>(stream));
+    return itq3s::launch_quantize(W, N, K, ldw, codes, scales, nullptr, status_flags, static_cast<hipStream_t>(stream));
 }
 
 int itq3s_roundtrip(const float* W, int64_t N, int64_t K, int64_t ldw, int block_size, uint8_t* codes_out, uint32_t* scales_out,
@@ -141,7 +141,7 @@ int itq3s_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, i
     if (out_dtype != ITQ3S_F32 && out_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
     if (!aligned(W_out, 16) || ldo % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
-    return itq3s::launch_dequantize(codes, scales, N, K, W_out, out_dtype == ITQ3S_F16, ldo, status_flags, static_cast<hipStream_t>(stream));
+    return itq3s::launch_dequantize(codes, scales, nullptr, N, K, W_out, out_dtype == ITQ3S_F16, ldo, status_flags, static_cast<hipStream_t>(stream));
 }
 
 int itq3s_matmul_grouped(const itq3s_weight* w, int count, int64_t K, const void* X, int64_t M, int64_t ldx, int y_dtype, void* workspace,
@@ -219,6 +219,58 @@ int itq3s_matmul(const uint32_t* codes, const uint32_t* scales, int64_t N, int64
     if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
     const itq3s_weight w = {codes, scales, N, Y, ldy};
     return itq3s_matmul_grouped(&w, 1, K, X, M, ldx, y_dtype, workspace, workspace_bytes, status_flags, stream);
+}
+
+// ---- the sub-block-scale variant of the format (116 bytes per block)
+
+size_t itq3s_subscales_bytes(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0 || K % 256 != 0) return 0;
+    return (size_t)((N + 15) / 16) * (size_t)(K / 256) * 256u;
+}
+
+int itq3s_quantize_sub(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* subscales,
+                       uint32_t* status_flags, void* stream) {
+    if (!subscales) return ITQ3S_ERR_NULL;
+    if (!aligned(subscales, 16)) return ITQ3S_ERR_ALIGN;
+    if (!W || !codes || !scales) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || K % 256 != 0 || ldw < K) return ITQ3S_ERR_SHAPE;
+    if (((N + 15) / 16) * (K / 256) > 0x3fffffffLL) return ITQ3S_ERR_SHAPE;
+    if (!aligned(W, 16) || ldw % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    return itq3s::launch_quantize(W, N, K, ldw, codes, scales, subscales, status_flags, static_cast<hipStream_t>(stream));
+}
+
+int itq3s_dequantize_sub(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, void* W_out,
+                         int out_dtype, int64_t ldo, uint32_t* status_flags, void* stream) {
+    if (!codes || !scales || !subscales || !W_out) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || K % 256 != 0 || ldo < K) return ITQ3S_ERR_SHAPE;
+    if (((N + 15) / 16) * (K / 256) > 0x7fffffffLL) return ITQ3S_ERR_SHAPE;
+    if (out_dtype != ITQ3S_F32 && out_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
+    if (!aligned(W_out, 16) || ldo % 4 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(subscales, 16) ||
+        (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    return itq3s::launch_dequantize(codes, scales, subscales, N, K, W_out, out_dtype == ITQ3S_F16, ldo, status_flags, static_cast<hipStream_t>(stream));
+}
+
+int itq3s_matmul_sub(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, const void* X, int64_t M,
+                     int64_t ldx, void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream) {
+    if (!codes || !scales || !subscales || !X || !Y) return ITQ3S_ERR_NULL;
+    if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
+    if (K > (1LL << 28) || 3 * ldx + K > (1LL << 29) || (N + 15) / 16 > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
+    if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
+    if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(subscales, 16) ||
+        !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) || (status_flags && !aligned(status_flags, 4)))
+        return ITQ3S_ERR_ALIGN;
+    // up to four rows per pass of the streaming kernel (it rotates the activations itself)
+    const size_t y_bytes = y_dtype == ITQ3S_F16 ? 2 : 4;
+    for (int64_t m0 = 0; m0 < M; m0 += itq3s::kGemvFusedMaxM) {
+        const int64_t rows = M - m0 < itq3s::kGemvFusedMaxM ? M - m0 : itq3s::kGemvFusedMaxM;
+        itq3s::GemvWeight gw{codes, scales, N, static_cast<unsigned char*>(Y) + (size_t)m0 * (size_t)ldy * y_bytes, ldy, subscales};
+        const int rc = itq3s::launch_gemv(&gw, 1, K, static_cast<const _Float16*>(X) + m0 * ldx, ldx, rows, y_dtype == ITQ3S_F16, status_flags,
+                                          static_cast<hipStream_t>(stream));
+        if (rc != 0) return rc;
+    }
+    return ITQ3S_OK;
 }
 
 int itq3s_matmul_static(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const void* X, int64_t M, int64_t ldx, void* Y,

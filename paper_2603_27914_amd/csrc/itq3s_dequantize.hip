@@ -20,9 +20,13 @@ namespace itq3s {
 // (at least two wavefronts per SIMD: with a register budget of 256 the matrix instructions write ordinary
 // vector registers; with the full 512 the compiler parks their results in accumulator registers and copies
 // every one of them out)
-template <bool kOutF16>
+// kSub: the sub-block-scale variant (Sec. 4.1: 116 bytes per block), w_hat = H( d (s_j q - z) ).  A lane's
+// four digits belong to sub-blocks 2g (the first two) and 2g+1, whose scales are the two halves of
+// the lane's own word of the sub-scale array; s q is exact in fp16, the first product (16 terms of one
+// sub-block: a 16-bit number) is carried in two fp16 parts, the second adds 16 such terms in fp32.
+template <bool kOutF16, bool kSub>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void dequantize_kernel(const uint32_t* __restrict__ codes, const uint32_t* __restrict__ scales,
-                                                         int64_t N, int KB, void* __restrict__ out, int64_t ldo,
+                                                         const uint32_t* __restrict__ subscales, int64_t N, int KB, void* __restrict__ out, int64_t ldo,
                                                          uint32_t* __restrict__ flags) {
     const int tile = (int)blockIdx.x;
     const int nt = tile / KB, b = tile - nt * KB;
@@ -38,9 +42,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     u32x4 lo[4];
     u32x2 hi[4];
     uint32_t sw[4];
+    uint32_t ssw[4];
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int r = wave * 4 + rr;
+        ssw[rr] = kSub ? subscales[(int64_t)tile * 64 + 16 * g + r] : 0u;
         // elements e = 64 g + 16 j + r16 (j = 0..3) sit in slot r16 of low-plane word j of storage lane
         // 16 g + r; their high bits in bit 16 (j & 1) + r16 of high-plane word j >> 1
         lo[rr] = *reinterpret_cast<const u32x4*>(t + 4 * (16 * g + r));
@@ -67,11 +73,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
         }
         const half2v bias = {(_Float16)(-1025.0f), (_Float16)(-1025.0f)};
         const half2v v01 = __builtin_bit_cast(half2v, p01 | 0x64006400u) + bias, v23 = __builtin_bit_cast(half2v, p23 | 0x64006400u) + bias;
-        const half4 v = {v01[0], v01[1], v23[0], v23[1]};
+        half4 v = {v01[0], v01[1], v23[0], v23[1]};
+        if constexpr (kSub) {
+            const _Float16 s_lo = __builtin_bit_cast(_Float16, (uint16_t)(ssw[rr] & 0xffffu)), s_hi = __builtin_bit_cast(_Float16, (uint16_t)(ssw[rr] >> 16));
+            v = half4{v[0] * s_lo, v[1] * s_lo, v[2] * s_hi, v[3] * s_hi};
+        }
         const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
         const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(v, h, zero, 0, 0, 0);  // V^T H_16, |.| <= 16 * 6
         const half4 th = {(_Float16)T[0], (_Float16)T[1], (_Float16)T[2], (_Float16)T[3]};
-        const floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);
+        floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);
+        if constexpr (kSub) {
+            const half4 tl = {(_Float16)(T[0] - (float)th[0]), (_Float16)(T[1] - (float)th[1]), (_Float16)(T[2] - (float)th[2]), (_Float16)(T[3] - (float)th[3])};
+            U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, tl, U, 0, 0, 0);
+        }
         const float d16 = f16_bits_to_f32(sw[rr] & 0xffffu) * 0.0625f;  // d / 16: exact, so one rounding per output as before
         const float z = f16_bits_to_f32(sw[rr] >> 16);
         float f[4] = {U[0], U[1], U[2], U[3]};
@@ -91,14 +105,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void d
     if (flags != nullptr && __builtin_amdgcn_ballot_w64(bad != 0u) != 0ull && lane == 0) atomicOr(flags, kFlagBadCode);
 }
 
-int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* out, int out_f16, int64_t ldo,
-                      uint32_t* flags, hipStream_t stream) {
+int launch_dequantize(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, void* out, int out_f16,
+                      int64_t ldo, uint32_t* flags, hipStream_t stream) {
     const int64_t tiles = ((N + 15) / 16) * (K / kBlock);
     const int KB = (int)(K / kBlock);
-    if (out_f16)
-        hipLaunchKernelGGL(dequantize_kernel<true>, dim3((unsigned)tiles), dim3(256), 0, stream, codes, scales, N, KB, out, ldo, flags);
-    else
-        hipLaunchKernelGGL(dequantize_kernel<false>, dim3((unsigned)tiles), dim3(256), 0, stream, codes, scales, N, KB, out, ldo, flags);
+    const dim3 grid((unsigned)tiles), block(256);
+    if (subscales != nullptr) {
+        if (out_f16) hipLaunchKernelGGL((dequantize_kernel<true, true>), grid, block, 0, stream, codes, scales, subscales, N, KB, out, ldo, flags);
+        else hipLaunchKernelGGL((dequantize_kernel<false, true>), grid, block, 0, stream, codes, scales, subscales, N, KB, out, ldo, flags);
+    } else {
+        if (out_f16) hipLaunchKernelGGL((dequantize_kernel<true, false>), grid, block, 0, stream, codes, scales, subscales, N, KB, out, ldo, flags);
+        else hipLaunchKernelGGL((dequantize_kernel<false, false>), grid, block, 0, stream, codes, scales, subscales, N, KB, out, ldo, flags);
+    }
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

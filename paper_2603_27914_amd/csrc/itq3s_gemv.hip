@@ -56,6 +56,7 @@ LaunchTiming take_launch_timing() {
 struct GemvTensor {
     const uint32_t* codes;
     const uint32_t* scales;
+    const uint32_t* subscales;  // the 116-byte variant's sub-scale array, or null
     void* Y;
     int64_t N, ldy;
     int v_begin;  // position of this tensor's first row tile in the list (0x7fffffff for unused entries)
@@ -75,6 +76,7 @@ struct TileRegs {
     u32x4 lo;
     u32x2 hi;
     uint32_t sc;
+    uint32_t ss;  // (sub-block variant) the lane's two sub-scales
 };
 
 __device__ __forceinline__ half8 as_half8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
@@ -140,7 +142,14 @@ __device__ __forceinline__ bool rotate_to_lds(u32x2 raw, const HadamardOperand& 
 // fetch of the unused descriptors, which are on the way to the first load).
 // NBC > 0: every wavefront has exactly NBC blocks (K = 2048 NBC): the pipeline is straight-line code,
 // which the compiler fits into 57..92 registers instead of 86..126 -- a third workgroup per compute unit.
-template <int MP, int RT, bool kGrouped, int NBC>
+// kSub: the sub-block-scale variant of the format (Sec. 4.1: 116 bytes per block), one tensor per launch:
+//   Y[m][n] = sum_b d ( sum_j s[n,b,j/32] (c-1)[n,b,j] x~[m,b,j]  -  z E[m,b] ).
+// A lane's 64 codes belong to two sub-blocks (low-plane words 0,1 and 2,3), whose scales are the two
+// halves of one more word per lane and tile.  The operand is the signed digit times the sub-scale:
+// (c 2^-14) (16 s) - s 2^-10 = (c-1) s 2^-10, exact in fp16 for 2^-4 <= s <= 4094 (the quantizer's
+// sub-scales lie below 3; smaller ones lose low bits of a contribution that is small anyway), so no
+// block sum S is needed.
+template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false>
 __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(const GemvArgs a) {
     constexpr int W = kGemvWaves;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -164,7 +173,7 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
 
     // Per slot: descriptors over the K range of the tile row in codes / scales (scalar selects; all
     // tensor entries come with the first argument fetch).
-    __amdgpu_buffer_rsrc_t crs[RT], srs[RT];
+    __amdgpu_buffer_rsrc_t crs[RT], srs[RT], urs[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         const uint32_t* t_codes = a.t[0].codes;
@@ -189,6 +198,7 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
         const int64_t first = have ? local * KB : 0;
         crs[rt] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(t_codes + first * kTileWords), 0, have ? KB * 1536 : 0, kRawBuffer);
         srs[rt] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(t_scales + first * kTileRows), 0, have ? KB * 64 : 0, kRawBuffer);
+        if constexpr (kSub) urs[rt] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.t[0].subscales + first * 64), 0, have ? KB * 256 : 0, kRawBuffer);
         if (threadIdx.x == 0) slot_out[rt] = SlotOut{t_y, t_ldy, local * 16, have ? t_n - local * 16 : 0};
     }
     // activations: rows beyond M read as zeros (offset outside the descriptor's range)
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
 
     constexpr uint32_t kOutside = 0x80000000u;  // an offset no descriptor here covers
     const uint32_t none = nb > 0 ? 0u : kOutside;  // a wavefront without blocks (K < 2048) loads nothing
-    const uint32_t off_lo = lane * 16 + none, off_hi = lane * 8 + 1024 + none, off_sc = r16 * 4 + none;
+    const uint32_t off_lo = lane * 16 + none, off_hi = lane * 8 + 1024 + none, off_sc = r16 * 4 + none, off_ss = lane * 4 + none;
     uint32_t off_x[MP];
 #pragma unroll
     for (int m = 0; m < MP; ++m) off_x[m] = m < a.M ? ((uint32_t)(m * a.ldx * 2) + (16 * r16 + 4 * g) * 2) | none : kOutside;
@@ -225,6 +235,7 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
             s.t[rt].lo = __builtin_amdgcn_raw_buffer_load_b128(crs[rt], off_lo, b * 1536, kLoadNT);
             s.t[rt].hi = __builtin_amdgcn_raw_buffer_load_b64(crs[rt], off_hi, b * 1536, kLoadNT);
             s.t[rt].sc = __builtin_amdgcn_raw_buffer_load_b32(srs[rt], off_sc, b * 64, kLoadNT);
+            if constexpr (kSub) s.t[rt].ss = __builtin_amdgcn_raw_buffer_load_b32(urs[rt], off_ss, b * 256, kLoadNT);
         }
     };
 
@@ -247,18 +258,32 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
         floatx4 c[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) c[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        half8 sub_mul[kSub ? RT : 1][2], sub_add[kSub ? RT : 1][2];  // (sub-block variant) 16 s and -s 2^-10 of the lane's two sub-blocks
+        if constexpr (kSub) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const half2v s2 = __builtin_bit_cast(half2v, s.t[rt].ss);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const _Float16 m = s2[h] * (_Float16)16.0f, n = s2[h] * (_Float16)(-0.0009765625f);
+                    sub_mul[rt][h] = half8{m, m, m, m, m, m, m, m};
+                    sub_add[rt][h] = half8{n, n, n, n, n, n, n, n};
+                }
+            }
+        }
         constexpr uint32_t kMask = 0x0C000C00u;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const half8 Xf = *reinterpret_cast<const half8*>(xs + ((t * 4 + g) * MP + mm) * 8);
-            sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf, ones, sacc, 0, 0, 0);
+            if constexpr (!kSub) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf, ones, sacc, 0, 0, 0);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 const uint32_t wds[4] = {s.t[rt].lo.x, s.t[rt].lo.y, s.t[rt].lo.z, s.t[rt].lo.w};
                 const uint32_t v = wds[t >> 1];
                 // slots j and j+8 of the word -> bits 11:10 and 27:26
-                const half8 op = (t & 1) == 0 ? as_half8((v << 10) & kMask, (v << 8) & kMask, (v << 6) & kMask, (v << 4) & kMask)
-                                              : as_half8((v << 2) & kMask, v & kMask, (v >> 2) & kMask, (v >> 4) & kMask);
+                half8 op = (t & 1) == 0 ? as_half8((v << 10) & kMask, (v << 8) & kMask, (v << 6) & kMask, (v << 4) & kMask)
+                                        : as_half8((v << 2) & kMask, v & kMask, (v >> 2) & kMask, (v >> 4) & kMask);
+                if constexpr (kSub) op = __builtin_elementwise_fma(op, sub_mul[rt][t >> 2], sub_add[rt][t >> 2]);  // words 0,1 | 2,3
                 c[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf, op, c[rt], 0, 0, 0);
             }
         }
@@ -269,7 +294,8 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
             const float z = f16_bits_to_f32(s.t[rt].sc >> 16);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                acc[rt][i] = __builtin_fmaf(d, __builtin_fmaf(c[rt][i] - sacc[i], 16384.0f, -z * ev[i]), acc[rt][i]);
+                acc[rt][i] = kSub ? __builtin_fmaf(d, __builtin_fmaf(c[rt][i], 1024.0f, -z * ev[i]), acc[rt][i])
+                                  : __builtin_fmaf(d, __builtin_fmaf(c[rt][i] - sacc[i], 16384.0f, -z * ev[i]), acc[rt][i]);
         }
     };
 
@@ -335,9 +361,9 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
     }
 }
 
-template <int MP, int RT, bool kGrouped, int NBC>
+template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false>
 static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
-    auto kern = gemv_kernel<MP, RT, kGrouped, NBC>;
+    auto kern = gemv_kernel<MP, RT, kGrouped, NBC, kSub>;
     const size_t lds = (size_t)kGemvWaves * MP * 512 + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
@@ -363,6 +389,14 @@ static int launch_shape(const GemvArgs& a, int grid, int rt, hipStream_t stream)
 
 template <int MP>
 static int launch_blocks(const GemvArgs& a, int grid, int rt, hipStream_t stream) {
+    if (a.t[0].subscales != nullptr) {  // the sub-block variant: one tensor, the general pipeline
+        switch (rt) {
+            case 1: return launch_kernel<MP, 1, false, 0, true>(a, grid, stream);
+            case 2: return launch_kernel<MP, 2, false, 0, true>(a, grid, stream);
+            case 3: return launch_kernel<MP, 3, false, 0, true>(a, grid, stream);
+        }
+        return -2;
+    }
     if (a.KB == 8) return launch_shape<MP, 1>(a, grid, rt, stream);
     if (a.KB == 16) return launch_shape<MP, 2>(a, grid, rt, stream);
     return launch_shape<MP, 0>(a, grid, rt, stream);
@@ -389,7 +423,8 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
     for (int i = 0; i < kGemvMaxGroup; ++i) {
         GemvTensor& t = a.t[i];
         if (i < count) {
-            t.codes = w[i].codes; t.scales = w[i].scales; t.Y = w[i].Y; t.N = w[i].N; t.ldy = w[i].ldy;
+            t.codes = w[i].codes; t.scales = w[i].scales; t.subscales = w[i].subscales; t.Y = w[i].Y; t.N = w[i].N; t.ldy = w[i].ldy;
+            if (t.subscales != nullptr && count != 1) return -2;
             if (nt_total > 0x7fffffff) return -2;
             t.v_begin = (int)nt_total;
             nt_total += (w[i].N + 15) / 16;
@@ -407,7 +442,7 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
     //  - otherwise: as many tiles as keep one workgroup per compute unit busy, at most three.
     const int cus = cu_count();
     int64_t grid64;
-    if (a.KB == 8 || a.KB == 16) {
+    if ((a.KB == 8 || a.KB == 16) && a.t[0].subscales == nullptr) {
         int64_t want = (nt_total + 3 * cus - 1) / (3 * cus);
         if (want > kGemvMaxRT) want = kGemvMaxRT;
         grid64 = (nt_total + want - 1) / want;

@@ -26,11 +26,13 @@ struct LaunchTiming {
 void set_launch_timing(hipEvent_t start, hipEvent_t stop);
 LaunchTiming take_launch_timing();
 
-int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* flags,
+// subscales: null for the 100-byte format; the sub-scale array of the 116-byte variant otherwise
+// (64 words per tile: word 16 g + r = fp16 s_2g | fp16 s_(2g+1) << 16 for tile row r, quarter g).
+int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* subscales, uint32_t* flags,
                     hipStream_t stream);
 
-int launch_dequantize(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, void* out, int out_f16, int64_t ldo,
-                      uint32_t* flags, hipStream_t stream);
+int launch_dequantize(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, void* out, int out_f16,
+                      int64_t ldo, uint32_t* flags, hipStream_t stream);
 
 // Rotated activations for the streaming path with 5..16 rows: Xt in MFMA operand order with MP (8 or
 // 16) columns; S[b*MP + m] = sum over the rounded rotated chunk, S[KB*MP + b*MP + m] = the exact
@@ -50,6 +52,7 @@ struct GemvWeight {
     int64_t N;
     void* Y;
     int64_t ldy;
+    const uint32_t* subscales = nullptr;  // the 116-byte variant's sub-scales (then the launch takes this one tensor only)
 };
 
 // count (1..kGemvMaxGroup) tensors W_t[N_t, K] against the same activations X[M][ldx], M <= kGemvFusedMaxM,

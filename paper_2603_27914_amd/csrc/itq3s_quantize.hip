@@ -54,11 +54,18 @@ __device__ __forceinline__ void cross_stage(double (&a)[E], int h) {
 // 11008x4096 / 28672x8192: 3.8 / 4.7 / 5.0 TB/s with 32 (110 registers, four wavefronts per SIMD),
 // 3.2 / 3.8 / 4.7 with 64 (168 registers, three per SIMD, and wavefronts so long that a tensor fills
 // the chip only a few times over); 16 elements per lane, the first version, ran at 3.3 / 3.6 / 4.3.
-template <int E>
+// kSub: the sub-block-scale variant of the format (Sec. 4.1: 8 fp16 sub-scales per block, 116 bytes).
+// A lane of the E = 32 arrangement holds exactly one sub-block (32 consecutive rotated coefficients), so
+// its deviation about the block mean is the lane's own partial of the pairwise sum; the sub-scale is
+// s_j = T* sigma_j / d (rounded to fp16 through fp32 like d), the digit thresholds become
+// (+-0.5 s_j - z) d, and d, z are those of the base format.  Lanes 2g, 2g+1 of a block share one
+// storage word: subscales[tile*64 + 16 g + r] = s_2g | s_(2g+1) << 16.
+template <int E, bool kSub>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(E == 64 ? 3 : 4))) void quantize_kernel(
     const float* __restrict__ W, int64_t N, int64_t K, int64_t ldw, uint32_t* __restrict__ codes, uint32_t* __restrict__ scales,
-    uint32_t* __restrict__ flags, int KB) {
+    uint32_t* __restrict__ subscales, uint32_t* __restrict__ flags, int KB) {
     static_assert(E == 32 || E == 64, "elements per lane");
+    static_assert(!kSub || E == 32, "a lane must hold one sub-block");
     constexpr int LB = kBlock / E, RW = 64 / LB, PARTS = kTileRows / RW, WPL = E / 16;  // WPL low-plane words per lane
     const int tile = (int)(blockIdx.x / PARTS), part = (int)(blockIdx.x % PARTS);  // tile = nt * KB + b
     const int nt = tile / KB, b = tile - nt * KB;
@@ -76,6 +83,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(E == 64 ? 3 
 #pragma unroll
     for (int i = 0; i < WPL; ++i) word[i] = 0x55555555u;  // codes "1" = digit 0
     uint32_t scale_word = 0u;
+    uint32_t sub_bits = 0u;
     if (n < N) {  // (uniform over the lanes of a block; the moves below never leave them)
         double a[E];
         const float4* src = reinterpret_cast<const float4*>(W + n * ldw + (int64_t)b * kBlock + E * h);
@@ -110,7 +118,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(E == 64 ? 3 
         // scalars instead of the elements, with bit-identical results.
         const double sum16 = block_lanes_sum<LB>(lane_tree_sum<E, 0, E>(a));
         const double mu = sum16 / 4096.0;                                                                     // mean of w'
-        const double sigma = sqrt(block_lanes_sum<LB>(lane_tree_sq<E, 0, E>(a, sum16 / 256.0)) / 65536.0);  // deviation of w'
+        const double lane_sq = lane_tree_sq<E, 0, E>(a, sum16 / 256.0);  // 256 x the squared deviations of the lane's coefficients
+        const double sigma = sqrt(block_lanes_sum<LB>(lane_sq) / 65536.0);  // deviation of w'
         // a non-finite weight makes every transformed value, hence the deviation, non-finite; finite
         // weights cannot (|w'| <= 16 * 3.4e38)
         const bool row_bad = !(__builtin_fabs(sigma) <= 1.7976931348623157e308);
@@ -124,8 +133,21 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(E == 64 ? 3 
         double z = 0.0 - rnd;
         if (z > 2048.0) { z = 2048.0; zclamp = true; }
         if (z < -2048.0) { z = -2048.0; zclamp = true; }
-        const double t_hi = (0.5 - z) * d * 16.0, t_lo = (-0.5 - z) * d * 16.0;  // exact products; against a = 16 w'
-        if (live) {
+        double step = 1.0;  // digit step in units of d
+        if constexpr (kSub) {
+            double s64 = kTStar * sqrt(lane_sq / 8192.0) / (live ? d : 1.0);  // T* sigma_j / d, sigma_j over the lane's 32 coefficients
+            if (s64 > 65504.0) { s64 = 65504.0; sat = true; }
+            const _Float16 sh = (_Float16)(float)s64;
+            step = (double)sh;
+            if (live) sub_bits = (uint32_t)__builtin_bit_cast(uint16_t, sh);
+        }
+        const double t_hi = (0.5 * step - z) * d * 16.0, t_lo = (-0.5 * step - z) * d * 16.0;  // exact products; against a = 16 w'
+        if (live && !(step > 0.0)) {
+            // (sub-block variant only) a sub-scale of zero: digit 0 everywhere in the sub-block
+            const _Float16 zh = (_Float16)(float)z;
+            scale_word = (uint32_t)__builtin_bit_cast(uint16_t, dh) | ((uint32_t)__builtin_bit_cast(uint16_t, zh) << 16);
+            if (zclamp) my_flags |= kFlagZClamp;
+        } else if (live) {
 #pragma unroll
             for (int i = 0; i < WPL; ++i) word[i] = 0u;
 #pragma unroll
@@ -145,6 +167,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(E == 64 ? 3 
     if constexpr (WPL == 4) *reinterpret_cast<u32x4*>(dst) = u32x4{word[0], word[1], word[2], word[3]};
     else *reinterpret_cast<u32x2*>(dst) = u32x2{word[0], word[1]};
     if (h == 0) scales[(int64_t)tile * kTileRows + r] = scale_word;
+    if constexpr (kSub) {
+        const uint32_t other = (uint32_t)row_xor_i32<1>((int)sub_bits);  // the neighbouring sub-block's scale
+        if ((h & 1) == 0) subscales[(int64_t)tile * 64 + 16 * (h >> 1) + r] = sub_bits | (other << 16);
+    }
     if (flags != nullptr && __builtin_amdgcn_ballot_w64(my_flags != 0u) != 0ull) {
         // one atomic per wavefront: OR of the flags of its lanes
         uint32_t f = my_flags;
@@ -154,11 +180,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(E == 64 ? 3 
     }
 }
 
-int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* flags,
+int launch_quantize(const float* W, int64_t N, int64_t K, int64_t ldw, uint32_t* codes, uint32_t* scales, uint32_t* subscales, uint32_t* flags,
                     hipStream_t stream) {
     const int64_t tiles = ((N + 15) / 16) * (K / kBlock);
     if (tiles > 0x3fffffff) return -2;
-    hipLaunchKernelGGL(quantize_kernel<32>, dim3((unsigned)(2 * tiles)), dim3(64), 0, stream, W, N, K, ldw, codes, scales, flags, (int)(K / kBlock));
+    if (subscales != nullptr)
+        hipLaunchKernelGGL((quantize_kernel<32, true>), dim3((unsigned)(2 * tiles)), dim3(64), 0, stream, W, N, K, ldw, codes, scales, subscales, flags, (int)(K / kBlock));
+    else
+        hipLaunchKernelGGL((quantize_kernel<32, false>), dim3((unsigned)(2 * tiles)), dim3(64), 0, stream, W, N, K, ldw, codes, scales, subscales, flags, (int)(K / kBlock));
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -25,6 +25,9 @@ csv.field_size_limit(1 << 30)
 
 def short(name):
     name = re.sub(r"\(.*$", "", name)
+    m = re.match(r"_ZN5itq3s(\d+)", name)  # a name the profiler left mangled
+    if m:
+        name = name[len(m.group(0)) : len(m.group(0)) + int(m.group(1))]
     return name.replace("void ", "").replace("itq3s::", "")
 
 
@@ -44,24 +47,34 @@ def gaps(path):
     for r in csv.DictReader(open(path)):
         rows.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), short(r["Kernel_Name"]), int(r.get("Grid_Size", r.get("Grid_Size_X", 0)) or 0)))
     rows.sort()
-    agg = collections.defaultdict(lambda: [0, 0.0, 0.0, 0])  # calls, duration, gap, gaps counted
+    # A dispatch counts as "inside a replayed step" if the dispatch before it is the streaming kernel
+    # too and ended less than 5 us earlier; launches of one template and grid that follow different
+    # launches (o after q+k+v, down after gate+up) are different shapes and are listed apart.
+    agg = collections.defaultdict(lambda: [0, 0.0, 0.0])  # calls, duration, gap
+    alone = collections.defaultdict(lambda: [0, 0.0])
     prev = None
     for st, en, name, grid in rows:
         if "gemv_kernel" in name:
-            a = agg[(name, grid)]
-            a[0] += 1
-            a[1] += en - st
-            if prev is not None and "gemv_kernel" in prev[2] and 0 <= st - prev[1] < 20000:
+            if prev is not None and "gemv_kernel" in prev[2] and 0 <= st - prev[1] < 5000:
+                a = agg[(name, grid, prev[2], prev[3])]
+                a[0] += 1
+                a[1] += en - st
                 a[2] += st - prev[1]
-                a[3] += 1
+            else:
+                alone[(name, grid)][0] += 1
+                alone[(name, grid)][1] += en - st
         prev = (st, en, name, grid)
-    print("%-40s %9s %7s %12s %14s" % ("kernel", "threads", "calls", "avg_ns", "avg_gap_ns"))
+    print("%-30s %8s  %-30s %8s %7s %11s %11s" % ("kernel", "threads", "follows", "threads", "calls", "avg_ns", "avg_gap_ns"))
     tot_d = tot_g = 0.0
-    for (name, grid), (calls, dur, gap, ng) in sorted(agg.items()):
-        print("%-40s %9d %7d %12.1f %14.1f" % (name[:40], grid, calls, dur / calls, gap / ng if ng else float("nan")))
+    for (name, grid, pname, pgrid), (calls, dur, gap) in sorted(agg.items()):
+        if calls < 8:
+            continue
+        print("%-30s %8d  %-30s %8d %7d %11.1f %11.1f" % (name[:30], grid, pname[:30], pgrid, calls, dur / calls, gap / calls))
         tot_d += dur / calls
-        tot_g += gap / ng if ng else 0.0
-    print("one launch of each shape: %.1f ns of kernel time + %.1f ns idle in front of them" % (tot_d, tot_g))
+        tot_g += gap / calls
+    print("one launch of each shape inside a replayed step: %.1f ns of kernel time + %.1f ns idle in front of them" % (tot_d, tot_g))
+    for (name, grid), (calls, dur) in sorted(alone.items()):
+        print("launched on its own (the timed passes: the host waits for every kernel): %-30s %8d %7d calls avg %.1f ns" % (name[:30], grid, calls, dur / calls))
 
 
 def pmc(path, copy_kib):
