@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libitq3s.so")
-SOURCES = ["itq3s_api.hip", "itq3s_quantize.hip", "itq3s_dequantize.hip", "itq3s_rotate.hip", "itq3s_gemv.hip", "itq3s_gemv_rows.hip", "itq3s_gemm.hip", "itq3s_gemm_ws.hip", "itq3s_probe.hip", "itq3s_ablation.hip"]
+SOURCES = ["itq3s_api.hip", "itq3s_quantize.hip", "itq3s_dequantize.hip", "itq3s_rotate.hip", "itq3s_gemv.hip", "itq3s_gemm.hip", "itq3s_gemm_ws.hip", "itq3s_probe.hip", "itq3s_ablation.hip"]
 FLAGS = [
     "--offload-arch=gfx950",
     "-O3",

@@ -31,6 +31,7 @@
 
 #include "itq3s_dev.h"
 #include <atomic>
+#include <type_traits>
 
 #include "itq3s_kernels.h"
 
@@ -65,7 +66,8 @@ struct GemvTensor {
 
 struct GemvArgs {
     GemvTensor t[kGemvMaxGroup];
-    const _Float16* X;  // activations [M][ldx]
+    const _Float16* X;  // activations [M][ldx]; kRotated: x~ in operand order with MP columns (from the rotation launch)
+    const float* S;     // kRotated: [2][KB][MP] sums of the rounded x~ per block and row, then 16 x[m][256 b]
     uint32_t* flags;
     int64_t ldx;
     int KB, M, y_f16;
@@ -149,8 +151,21 @@ __device__ __forceinline__ bool rotate_to_lds(u32x2 raw, const HadamardOperand& 
 // (c 2^-14) (16 s) - s 2^-10 = (c-1) s 2^-10, exact in fp16 for 2^-4 <= s <= 4094 (the quantizer's
 // sub-scales lie below 3; smaller ones lose low bits of a contribution that is small anyway), so no
 // block sum S is needed.
-template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false>
+// kRotated (5..16 rows, MP = 8 or 16): the activations arrive rotated, in operand order, from a launch
+// of their own (rotating 8 or 16 rows per block inside every workgroup would cost more than the
+// contraction); a wavefront loads the eight fragments and the two sums of its next block straight into
+// registers right behind the arithmetic of the current one, in front of the next tile loads, so that
+// the in-order load counter never makes it wait for those.
+// NSG = 2 (kRotated only): the workgroup owns 2 RT row tiles; a wavefront multiplies the fragments of a
+// block with the first RT tiles, then with the other RT (two pipeline steps per block), so that every
+// fragment fetched -- the bulk of what a workgroup pulls through its L1 with 16 rows -- serves twice
+// the weights, and its latency is met once per two steps.
+template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false, bool kRotated = false, int NSG = 1>
 __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(const GemvArgs a) {
+    static_assert(!kRotated || (NBC == 0 && !kSub && MP >= 8), "rotated activations: general pipeline, base format");
+    static_assert(kRotated || MP <= 4, "in-kernel rotation: at most four rows");
+    static_assert(NSG == 1 || (NSG == 2 && kRotated), "row sub-groups: with rotated activations only");
+    constexpr int RTW = RT * NSG;  // row tiles of the workgroup
     constexpr int W = kGemvWaves;
     extern __shared__ __align__(16) unsigned char smem[];
     const int KB = a.KB;
@@ -166,16 +181,17 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
         int64_t n0;    // first row of the tile inside its tensor
         int64_t rows;  // rows of that tensor from n0 on that exist (<= 0: slot unused)
     };
-    // LDS: per wavefront MP*512 bytes of x~ | red: W*RT*MP*16 floats | slot_out[RT]
+    // LDS: per wavefront MP*512 bytes of x~ (in-kernel rotation only) | red: W*RTW*MP*16 floats | slot_out[RTW]
+    constexpr size_t kXsBytes = kRotated ? 0 : (size_t)W * MP * 512;
     _Float16* const xs = reinterpret_cast<_Float16*>(smem) + (size_t)wave * MP * 256;
-    float* const red = reinterpret_cast<float*>(smem + (size_t)W * MP * 512);
-    SlotOut* const slot_out = reinterpret_cast<SlotOut*>(smem + (size_t)W * MP * 512 + (size_t)W * RT * MP * 16 * 4);
+    float* const red = reinterpret_cast<float*>(smem + kXsBytes);
+    SlotOut* const slot_out = reinterpret_cast<SlotOut*>(smem + kXsBytes + (size_t)W * RTW * MP * 16 * 4);
 
     // Per slot: descriptors over the K range of the tile row in codes / scales (scalar selects; all
     // tensor entries come with the first argument fetch).
-    __amdgpu_buffer_rsrc_t crs[RT], srs[RT], urs[RT];
+    __amdgpu_buffer_rsrc_t crs[RTW], srs[RTW], urs[kSub ? RTW : 1];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
+    for (int rt = 0; rt < RTW; ++rt) {
         const uint32_t* t_codes = a.t[0].codes;
         const uint32_t* t_scales = a.t[0].scales;
         void* t_y = a.t[0].Y;
@@ -202,56 +218,82 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
         if (threadIdx.x == 0) slot_out[rt] = SlotOut{t_y, t_ldy, local * 16, have ? t_n - local * 16 : 0};
     }
     // activations: rows beyond M read as zeros (offset outside the descriptor's range)
-    const __amdgpu_buffer_rsrc_t xrs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<_Float16*>(a.X), 0, (int)(((int64_t)(a.M - 1) * a.ldx + (int64_t)KB * 256) * 2), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<_Float16*>(a.X), 0, kRotated ? KB * MP * 512 : (int)(((int64_t)(a.M - 1) * a.ldx + (int64_t)KB * 256) * 2), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t sumrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.S), 0, kRotated ? 2 * KB * MP * 4 : 0, kRawBuffer);
     const int nb = KB > wave ? (KB - wave + W - 1) / W : 0;  // blocks of this wavefront: b = wave + j*W
 
     constexpr uint32_t kOutside = 0x80000000u;  // an offset no descriptor here covers
     const uint32_t none = nb > 0 ? 0u : kOutside;  // a wavefront without blocks (K < 2048) loads nothing
     const uint32_t off_lo = lane * 16 + none, off_hi = lane * 8 + 1024 + none, off_sc = r16 * 4 + none, off_ss = lane * 4 + none;
-    uint32_t off_x[MP];
+    uint32_t off_x[kRotated ? 1 : MP];
+    if constexpr (!kRotated) {
 #pragma unroll
-    for (int m = 0; m < MP; ++m) off_x[m] = m < a.M ? ((uint32_t)(m * a.ldx * 2) + (16 * r16 + 4 * g) * 2) | none : kOutside;
+        for (int m = 0; m < MP; ++m) off_x[m] = m < a.M ? ((uint32_t)(m * a.ldx * 2) + (16 * r16 + 4 * g) * 2) | none : kOutside;
+    }
+    // rotated activations: fragment t of the block for lane (row mm, quarter g) at ((t*4 + g)*MP + mm)*16 bytes
+    const uint32_t off_xf = (uint32_t)((g * MP + mm) * 16) + none, off_sum = (uint32_t)(((4 * g) & (MP - 1)) * 4) + none;
+    half8 xf[kRotated ? 8 : 1];
+    floatx4 sv_r = {0.f, 0.f, 0.f, 0.f}, ev_r = {0.f, 0.f, 0.f, 0.f};
+    auto issue_x = [&](int j) {  // fragments and sums of step j (kRotated)
+        const int b = nb > 0 ? wave + j * W : 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            xf[t] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(xrs, off_xf + (uint32_t)(t * 4 * MP * 16), b * (MP * 512), 0));
+        sv_r = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(sumrs, off_sum, b * (MP * 4), 0));
+        ev_r = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(sumrs, off_sum, (KB + b) * (MP * 4), 0));
+    };
 
-    floatx4 acc[RT];
+    floatx4 acc[RTW];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) acc[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < RTW; ++rt) acc[rt] = floatx4{0.f, 0.f, 0.f, 0.f};
     uint32_t bad = 0;
     bool in_range = true;
 
     struct Slot {
         TileRegs t[RT];
-        u32x2 xr[MP];
+        u32x2 xr[kRotated ? 1 : MP];
     };
     Slot ring[2];
 
     // loads of step j: the wavefront's activations of block wave + j*W, then that block of every row tile
-    auto issue = [&](Slot& s, int j) {
+    // (of sub-group SG of the row tiles)
+    auto issue_sg = [&](Slot& s, int j, auto sgc) {
+        constexpr int SG = decltype(sgc)::value;
         const int b = nb > 0 ? wave + j * W : 0;
+        if constexpr (!kRotated) {
 #pragma unroll
-        for (int m = 0; m < MP; ++m) s.xr[m] = __builtin_amdgcn_raw_buffer_load_b64(xrs, off_x[m], b * 512, 0);
+            for (int m = 0; m < MP; ++m) s.xr[m] = __builtin_amdgcn_raw_buffer_load_b64(xrs, off_x[m], b * 512, 0);
+        }
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            s.t[rt].lo = __builtin_amdgcn_raw_buffer_load_b128(crs[rt], off_lo, b * 1536, kLoadNT);
-            s.t[rt].hi = __builtin_amdgcn_raw_buffer_load_b64(crs[rt], off_hi, b * 1536, kLoadNT);
-            s.t[rt].sc = __builtin_amdgcn_raw_buffer_load_b32(srs[rt], off_sc, b * 64, kLoadNT);
+            s.t[rt].lo = __builtin_amdgcn_raw_buffer_load_b128(crs[SG * RT + rt], off_lo, b * 1536, kLoadNT);
+            s.t[rt].hi = __builtin_amdgcn_raw_buffer_load_b64(crs[SG * RT + rt], off_hi, b * 1536, kLoadNT);
+            s.t[rt].sc = __builtin_amdgcn_raw_buffer_load_b32(srs[SG * RT + rt], off_sc, b * 64, kLoadNT);
             if constexpr (kSub) s.t[rt].ss = __builtin_amdgcn_raw_buffer_load_b32(urs[rt], off_ss, b * 256, kLoadNT);
         }
     };
+    auto issue = [&](Slot& s, int j) { issue_sg(s, j, std::integral_constant<int, 0>{}); };
 
     HadamardOperand H;
     H.init(lane);
     const half8 ones = as_half8(0x04000400u, 0x04000400u, 0x04000400u, 0x04000400u);  // 2^-14 each
 
-    auto compute = [&](const Slot& s) {
-#pragma unroll
-        for (int m = 0; m < MP; ++m) in_range = rotate_to_lds<MP>(s.xr[m], H, lane, m, xs) && in_range;
-        // lane 0 holds x[0..3] of the chunk: E = 16 x_0 (rows m = 4g + i of the accumulators are row i & (MP-1) for M <= 4)
+    auto compute_sg = [&](const Slot& s, auto sgc) {
+        constexpr int SG = decltype(sgc)::value;
         float ev[4];
+        if constexpr (kRotated) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s.xr[i & (MP - 1)].x);
-            ev[i] = 16.0f * f16_bits_to_f32(w0 & 0xffffu);
+            for (int i = 0; i < 4; ++i) ev[i] = ev_r[i];
+        } else {
+#pragma unroll
+            for (int m = 0; m < MP; ++m) in_range = rotate_to_lds<MP>(s.xr[m], H, lane, m, xs) && in_range;
+            // lane 0 holds x[0..3] of the chunk: E = 16 x_0 (rows m = 4g + i of the accumulators are row i & (MP-1) for M <= 4)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s.xr[i & (MP - 1)].x);
+                ev[i] = 16.0f * f16_bits_to_f32(w0 & 0xffffu);
+            }
         }
         // the block sums S come from the matrix cores as well: the same fragments against an operand of ones
         floatx4 sacc = {0.f, 0.f, 0.f, 0.f};
@@ -274,8 +316,10 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
         constexpr uint32_t kMask = 0x0C000C00u;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const half8 Xf = *reinterpret_cast<const half8*>(xs + ((t * 4 + g) * MP + mm) * 8);
-            if constexpr (!kSub) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf, ones, sacc, 0, 0, 0);
+            half8 Xf;
+            if constexpr (kRotated) Xf = xf[t];
+            else Xf = *reinterpret_cast<const half8*>(xs + ((t * 4 + g) * MP + mm) * 8);
+            if constexpr (!kSub && !kRotated) sacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(Xf, ones, sacc, 0, 0, 0);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 const uint32_t wds[4] = {s.t[rt].lo.x, s.t[rt].lo.y, s.t[rt].lo.z, s.t[rt].lo.w};
@@ -294,14 +338,17 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
             const float z = f16_bits_to_f32(s.t[rt].sc >> 16);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                acc[rt][i] = kSub ? __builtin_fmaf(d, __builtin_fmaf(c[rt][i], 1024.0f, -z * ev[i]), acc[rt][i])
-                                  : __builtin_fmaf(d, __builtin_fmaf(c[rt][i] - sacc[i], 16384.0f, -z * ev[i]), acc[rt][i]);
+                acc[SG * RT + rt][i] = kSub       ? __builtin_fmaf(d, __builtin_fmaf(c[rt][i], 1024.0f, -z * ev[i]), acc[SG * RT + rt][i])
+                                       : kRotated ? __builtin_fmaf(d, __builtin_fmaf(c[rt][i], 16384.0f, -__builtin_fmaf(z, ev[i], sv_r[i])), acc[SG * RT + rt][i])
+                                                  : __builtin_fmaf(d, __builtin_fmaf(c[rt][i] - sacc[i], 16384.0f, -z * ev[i]), acc[SG * RT + rt][i]);
         }
     };
+    auto compute = [&](const Slot& s) { compute_sg(s, std::integral_constant<int, 0>{}); };
 
     // ---- pipeline, one step ahead; every load issued belongs to a real step (the scheduling
     // barriers keep the loads in front of the arithmetic they overlap with)
     issue(ring[0], 0);
+    if constexpr (kRotated) issue_x(0);
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (NBC > 0) {
 #pragma unroll
@@ -311,6 +358,29 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
             compute(ring[q & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
+    } else if constexpr (NSG == 2) {
+        // two steps per block: ring[0] carries the first RT row tiles of a block, ring[1] the others
+        constexpr std::integral_constant<int, 0> sg0{};
+        constexpr std::integral_constant<int, 1> sg1{};
+        int j = 0;
+        for (; j + 1 < nb; ++j) {
+            issue_sg(ring[1], j, sg1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_sg(ring[0], sg0);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_sg(ring[0], j + 1, sg0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_sg(ring[1], sg1);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_x(j + 1);
+        }
+        if (nb > 0) {
+            issue_sg(ring[1], j, sg1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_sg(ring[0], sg0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_sg(ring[1], sg1);
+        }
     } else {
         int j = 0;
         for (; j + 2 < nb; j += 2) {
@@ -318,15 +388,19 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
             __builtin_amdgcn_sched_barrier(0);
             compute(ring[0]);
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (kRotated) issue_x(j + 1);
             issue(ring[0], j + 2);
             __builtin_amdgcn_sched_barrier(0);
             compute(ring[1]);
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (kRotated) issue_x(j + 2);
         }
         if (j + 2 == nb) {
             issue(ring[1], j + 1);
             __builtin_amdgcn_sched_barrier(0);
             compute(ring[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (kRotated) issue_x(j + 1);
             __builtin_amdgcn_sched_barrier(0);
             compute(ring[1]);
         } else if (j + 1 == nb) {
@@ -337,19 +411,19 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
     // ---- add the W partial sums of every output, store Y.  red[wave][rt][m][r]; slot_out says where
     // the 16 outputs of a slot go.
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
+    for (int rt = 0; rt < RTW; ++rt)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (4 * g + i < MP) red[((wave * RT + rt) * MP + 4 * g + i) * 16 + r16] = acc[rt][i];
+            if (4 * g + i < MP) red[((wave * RTW + rt) * MP + 4 * g + i) * 16 + r16] = acc[rt][i];
     __syncthreads();
-    for (int o = threadIdx.x; o < RT * 16 * MP; o += W * 64) {
-        const int rr = o % (RT * 16), m = o / (RT * 16);  // rr = rt*16 + r: consecutive threads, consecutive n
+    for (int o = threadIdx.x; o < RTW * 16 * MP; o += W * 64) {
+        const int rr = o % (RTW * 16), m = o / (RTW * 16);  // rr = rt*16 + r: consecutive threads, consecutive n
         const int rt = rr >> 4, r = rr & 15;
         const SlotOut so = slot_out[rt];
         if (r < so.rows && m < a.M) {
             float sum = 0.f;
 #pragma unroll
-            for (int wv = 0; wv < W; ++wv) sum += red[((wv * RT + rt) * MP + m) * 16 + r];
+            for (int wv = 0; wv < W; ++wv) sum += red[((wv * RTW + rt) * MP + m) * 16 + r];
             const int64_t n = so.n0 + r;
             if (a.y_f16) reinterpret_cast<_Float16*>(so.Y)[m * so.ldy + n] = (_Float16)sum;
             else reinterpret_cast<float*>(so.Y)[m * so.ldy + n] = sum;
@@ -361,10 +435,10 @@ __global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(
     }
 }
 
-template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false>
+template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false, bool kRotated = false, int NSG = 1>
 static int launch_kernel(const GemvArgs& a, int grid, hipStream_t stream) {
-    auto kern = gemv_kernel<MP, RT, kGrouped, NBC, kSub>;
-    const size_t lds = (size_t)kGemvWaves * MP * 512 + (size_t)kGemvWaves * RT * MP * 16 * 4 + (size_t)RT * 32;
+    auto kern = gemv_kernel<MP, RT, kGrouped, NBC, kSub, kRotated, NSG>;
+    const size_t lds = (kRotated ? 0 : (size_t)kGemvWaves * MP * 512) + (size_t)kGemvWaves * RT * NSG * MP * 16 * 4 + (size_t)RT * NSG * 32;
     const LaunchTiming tm = take_launch_timing();
     if (tm.start != nullptr) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, tm.start, tm.stop, 0, a);
     else hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvWaves * 64), lds, stream, a);
@@ -414,18 +488,15 @@ int cu_count() {
     return n;
 }
 
-int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, int64_t M, int y_f16, uint32_t* flags,
-                hipStream_t stream) {
-    if (count < 1 || count > kGemvMaxGroup || M < 1 || M > kGemvFusedMaxM) return -2;
-    GemvArgs a;
-    a.X = X; a.flags = flags; a.ldx = ldx; a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
+// Fills the tensor list of a launch; returns the number of row tiles, or -1.
+static int64_t fill_tensors(GemvArgs& a, const GemvWeight* w, int count) {
     int64_t nt_total = 0;
     for (int i = 0; i < kGemvMaxGroup; ++i) {
         GemvTensor& t = a.t[i];
         if (i < count) {
             t.codes = w[i].codes; t.scales = w[i].scales; t.subscales = w[i].subscales; t.Y = w[i].Y; t.N = w[i].N; t.ldy = w[i].ldy;
-            if (t.subscales != nullptr && count != 1) return -2;
-            if (nt_total > 0x7fffffff) return -2;
+            if (t.subscales != nullptr && count != 1) return -1;
+            if (nt_total > 0x7fffffff) return -1;
             t.v_begin = (int)nt_total;
             nt_total += (w[i].N + 15) / 16;
         } else {
@@ -434,7 +505,16 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
         }
         t.pad_ = 0;
     }
-    if (nt_total >= 0x7fffffff) return -2;
+    return nt_total < 0x7fffffff ? nt_total : -1;
+}
+
+int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, int64_t ldx, int64_t M, int y_f16, uint32_t* flags,
+                hipStream_t stream) {
+    if (count < 1 || count > kGemvMaxGroup || M < 1 || M > kGemvFusedMaxM) return -2;
+    GemvArgs a;
+    a.X = X; a.S = nullptr; a.flags = flags; a.ldx = ldx; a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
+    const int64_t nt_total = fill_tensors(a, w, count);
+    if (nt_total < 0) return -2;
     // Row tiles per workgroup (every workgroup rotates all of X for itself, so more tiles per workgroup
     // mean less of that; fewer mean more workgroups in flight).  Measured on the 7B and 70B shapes:
     //  - K = 2048 or 4096 (a wavefront walks one or two blocks; three or four workgroups fit a compute
@@ -463,6 +543,40 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
         case 2: return launch_blocks<2>(a, grid, rt, stream);
         default: return launch_blocks<4>(a, grid, rt, stream);
     }
+}
+
+template <int MP>
+static int launch_rotated(const GemvArgs& a, int grid, int rt, hipStream_t stream) {
+    const bool grouped = a.t[1].v_begin != 0x7fffffff;
+    switch (rt) {
+        case 1: return grouped ? launch_kernel<MP, 1, true, 0, false, true>(a, grid, stream) : launch_kernel<MP, 1, false, 0, false, true>(a, grid, stream);
+        case 2: return grouped ? launch_kernel<MP, 2, true, 0, false, true>(a, grid, stream) : launch_kernel<MP, 2, false, 0, false, true>(a, grid, stream);
+        case 3: case 4: return grouped ? launch_kernel<MP, 2, true, 0, false, true, 2>(a, grid, stream) : launch_kernel<MP, 2, false, 0, false, true, 2>(a, grid, stream);
+    }
+    return -2;
+}
+
+int launch_gemv_rows(const GemvWeight* w, int count, int64_t K, const _Float16* Xt, const float* S, int64_t M, int MP, int y_f16,
+                     uint32_t* flags, hipStream_t stream) {
+    if (count < 1 || count > kGemvMaxGroup || M <= kGemvFusedMaxM || M > kGemvMaxM || (MP != 8 && MP != 16) || M > MP) return -2;
+    GemvArgs a;
+    a.X = Xt; a.S = S; a.flags = flags; a.ldx = 0; a.KB = (int)(K / kBlock); a.M = (int)M; a.y_f16 = y_f16;
+    const int64_t nt_total = fill_tensors(a, w, count);
+    if (nt_total < 0) return -2;
+    // Every workgroup pulls all of the rotated activations (2 MP K bytes) through its compute unit's
+    // L1: as many row tiles per workgroup as keep every compute unit busy, at most four (two steps of
+    // two tiles per block).
+    const int cus = cu_count();
+    int64_t want = (nt_total + cus - 1) / cus;
+    if (want > 4) want = 4;
+    int64_t grid64 = (nt_total + want - 1) / want;
+    if (grid64 < cus && nt_total >= cus) grid64 = cus;
+    if (grid64 > 0x7fffffff) return -2;
+    const int grid = (int)grid64;
+    const int rt = (int)((nt_total + grid - 1) / grid);
+    a.nt_q = (int)(nt_total / grid);
+    a.nt_r = (int)(nt_total % grid);
+    return MP == 8 ? launch_rotated<8>(a, grid, rt, stream) : launch_rotated<16>(a, grid, rt, stream);
 }
 
 }  // namespace itq3s
