@@ -1,4 +1,6 @@
-// Streaming matmul for M <= 4 activation rows (the decode path, Sec. 5.4).
+// Streaming matmul for M <= 16 activation rows (the decode path, Sec. 5.4).  The description below is
+// the kernel for M <= 4, which rotates the activations itself; the variant for 5..16 rows, which
+// takes them rotated from a launch in front, is described at the kernel template.
 //
 //   Y[m][n] = sum_b d[n,b] * ( sum_j c[n,b,j] x~[m,b,j]  -  S[m,b]  -  z[n,b] * E[m,b] )
 //
