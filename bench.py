@@ -419,7 +419,10 @@ def prefill_leg(torch, binding, synth, gen, m_list=(512, 2048)):
                         "kernel_us": round(kms * 1e3, 1), "kernel_TFLOPs": round(2.0 * M * N * K / (kms * 1e-3) / 1e12, 1),
                         "kernel_frac_of_mfma_peak": round(2.0 * M * N * K / (kms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
                         "weight_side_kernel_us": round(wms * 1e3, 1), "weight_side_TFLOPs": round(2.0 * M * N * K / (wms * 1e-3) / 1e12, 1),
-                        "weight_side_overhead_pct": round(100.0 * (wms / kms - 1.0), 1)})
+                        "weight_side_overhead_pct": round(100.0 * (wms / kms - 1.0), 1),
+                        # workgroups per launch: the weight-side kernel (512 x 128 tiles, no split of K) fills the chip only
+                        # when it has at least one per compute unit -- compare the overhead where both kernels do
+                        "weight_side_workgroups": ((M + 511) // 512) * ((N + 127) // 128)})
     return res
 
 

@@ -156,9 +156,10 @@ int itq3s_matmul_grouped(const itq3s_weight *w, int count, int64_t K, const void
  * every 256-channel block of a weight tile is unpacked, scaled and passed through the inverse
  * transform on its way into on-chip memory, then multiplied with the un-rotated activations on the
  * matrix cores; no dequantized weight is written to memory and no workspace is needed.  Results
- * agree with itq3s_matmul within the same tolerance (the rounding sits on w_hat instead of H x).  It
- * repeats the transform for every 128-row slab of X and is meant for comparing the two placements,
- * not as the fast path.  Arguments as for itq3s_matmul; any M with ceil(M/128) <= 65535.
+ * agree with itq3s_matmul within the same tolerance (the rounding sits on w_hat instead of H x).  A
+ * reconstructed 128-row weight tile is shared by 512 rows of X, so the transform of the whole tensor
+ * is repeated ceil(M/512) times; the call is meant for comparing the two placements, not as the fast
+ * path.  Arguments as for itq3s_matmul; any M with ceil(M/512) <= 65535.
  * (A variant that also reports the kernel's duration is declared in itq3s_bench.h.) */
 int itq3s_matmul_weight_side(const uint32_t *codes, const uint32_t *scales, int64_t N, int64_t K, const void *X, int64_t M,
                              int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags, void *stream);

@@ -287,7 +287,7 @@ int itq3s_matmul_weight_side(const uint32_t* codes, const uint32_t* scales, int6
                              void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream) {
     if (!codes || !scales || !X || !Y) return ITQ3S_ERR_NULL;
     if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
-    if ((N + 15) / 16 > 0x7fffffffLL / (K / 256) || (M + 127) / 128 > 65535) return ITQ3S_ERR_SHAPE;
+    if ((N + 15) / 16 > 0x7fffffffLL / (K / 256) || (M + 511) / 512 > 65535) return ITQ3S_ERR_SHAPE;
     if (y_dtype != ITQ3S_F32 && y_dtype != ITQ3S_F16) return ITQ3S_ERR_DTYPE;
     if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) ||
         (status_flags && !aligned(status_flags, 4)))

@@ -6,15 +6,25 @@
 //   Y[m][n] = sum_k x[m][k] * w_hat[n][k],   w_hat = H( d (q - z) )   rounded once to fp16
 //
 // The library's default path rotates the activations instead (itq3s_gemm.hip); this kernel exists to
-// measure what the weight-side placement costs on this machine: the transform work is repeated for
-// every 128-row slab of activations that meets the weight tile.
+// measure what the weight-side placement costs on this machine when it is done as well as the
+// placement allows: a reconstructed weight tile stays in LDS and is multiplied with as many
+// activation rows as one workgroup's accumulators can hold.
 //
-// Workgroup: 256 threads = 2 x 2 wavefronts, tile 128 (m) x 128 (n) x 256 (k = one block), wavefront
-// tile 64 x 64 as 2 x 2 v_mfma_f32_32x32x16_f16.  Per block step the workgroup copies a 128 x 256
-// slab of X into LDS and reconstructs 128 weight rows: a wavefront takes one row at a time, each lane
-// extracts its four codes, and two 16x16x16 products give the transposed 256-point transform
-// (H_256 = H_16 (x) H_16, all integers exact), leaving every lane with four consecutive channels;
-// the zero-point reaches only channel 0 (H 1 = 16 e_0), in fp32 before the rounding.
+// Workgroup: 512 threads = 4 (m) x 2 (n) wavefronts, tile 512 (m) x 128 (n), K in blocks of 256;
+// wavefront tile 128 x 64 = 4 x 2 v_mfma_f32_32x32x16_f16 (128 accumulator registers).  The
+// transform of a 128 x 256 weight tile is thus shared by 512 activation rows (it is repeated
+// ceil(M / 512) times in all; for M <= 512 exactly once).
+//
+// Per block:  (1) every wavefront reconstructs one 16-row storage tile into the LDS weight tile.  Its
+// packed words -- loaded one block ahead, 28 bytes per lane -- go through a wavefront-private LDS
+// stage, from which the 16 lanes of a group read row r's words by broadcast; per row, every lane
+// extracts its four codes and two 16x16x16 products give the transposed 256-point transform
+// (H_256 = H_16 (x) H_16, all integers exact), leaving every lane with four consecutive channels; the
+// zero-point reaches only channel 0 (H 1 = 16 e_0), in fp32 before the one rounding to fp16.  Four
+// rows run as independent chains.  (2) eight steps of 32 channels: the activations of a step
+// (512 x 32) are loaded two steps ahead into registers and parked in one of two LDS buffers, one
+// barrier per step.  The reconstruction is not overlapped with the products of another block: what
+// it costs is what the placement costs.
 #include <hip/hip_ext.h>
 
 #include "itq3s_dev.h"
@@ -24,9 +34,13 @@
 
 namespace itq3s {
 
-constexpr int WM = 128, WN = 128, WK = 256;
-constexpr int WLD = WK + 8;                     // LDS row stride in halves (528 bytes: 16-byte reads conflict-free)
-constexpr int kGemmWsLds = 2 * WM * WLD * 2;    // bytes: X slab + weight slab
+constexpr int WM = 512, WN = 128, WK = 256, WSTEP = 32;
+constexpr int WLD = WK + 8;                   // weight tile row stride in halves (528 bytes: 16-byte reads conflict-free)
+constexpr int XLD = WSTEP + 8;                // activation buffer row stride in halves (80 bytes)
+constexpr int kWsStageWords = 416;            // per wavefront: 256 low-plane + 128 high-plane words, 16 x (d / 16, 256 z) as floats
+constexpr int kWsBsBytes = WN * WLD * 2;      // 67584
+constexpr int kWsAsBytes = WM * XLD * 2;      // 40960 per buffer
+constexpr int kGemmWsLds = kWsBsBytes + 2 * kWsAsBytes + 8 * kWsStageWords * 4;  // 162816 of 163840
 
 struct GemmWsArgs {
     const uint32_t* codes;
@@ -38,13 +52,11 @@ struct GemmWsArgs {
     int NT, KB, y_f16;
 };
 
-// (at least two wavefronts per SIMD: with a register budget of 256 the matrix instructions write ordinary
-// vector registers; with the full 512 the compiler parks their results in accumulator registers and copies
-// every one of them out)
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void gemm_ws_kernel(const GemmWsArgs a) {
-    extern __shared__ __align__(16) _Float16 lds[];
-    _Float16* const As = lds;             // [WM][WLD] activations
-    _Float16* const Bs = lds + WM * WLD;  // [WN][WLD] reconstructed weights
+__global__ __launch_bounds__(512) void gemm_ws_kernel(const GemmWsArgs a) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    _Float16* const Bs = reinterpret_cast<_Float16*>(lds_raw);                       // [WN][WLD] reconstructed weights of the block
+    _Float16* const As = reinterpret_cast<_Float16*>(lds_raw + kWsBsBytes);          // [2][WM][XLD] activations of a step
+    uint32_t* const stage_all = reinterpret_cast<uint32_t*>(lds_raw + kWsBsBytes + 2 * kWsAsBytes);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -52,92 +64,131 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void g
     const int r16 = lane & 15, g = lane >> 4;
     const int64_t m0 = (int64_t)blockIdx.y * WM;
     const int64_t n0 = (int64_t)blockIdx.x * WN;
+    uint32_t* const stage = stage_all + wave * kWsStageWords;
 
     half4 h;  // H_16[4g + j][r16]: B operand of the first product, A operand of the second
 #pragma unroll
     for (int j = 0; j < 4; ++j) h[j] = (__builtin_popcount((4 * g + j) & r16) & 1) ? (_Float16)(-1.0f) : (_Float16)1.0f;
 
-    floatx16 acc[2][2];
+    // the wavefront's storage tile: rows n0 + 16 wave ..; a tile beyond the tensor is read from the last
+    // valid one and scaled by zero
+    const int my_tile = (int)(n0 >> 4) + wave;
+    const bool tile_ok = my_tile < a.NT;
+    const int64_t tile_base = (int64_t)(tile_ok ? my_tile : a.NT - 1) * a.KB;
+
+    // activations: thread t carries pieces t, t + 512, t + 1024, t + 1536 of a step (piece = 16 bytes; four per row)
+    const _Float16* xp[4];
+    bool xok[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 512 * i, row = idx >> 2, c = idx & 3;
+        const int64_t m = m0 + row;
+        xok[i] = m < a.M;
+        xp[i] = a.X + (xok[i] ? m : 0) * a.ldx + c * 8;
+    }
+    const int total_steps = a.KB * (WK / WSTEP);
+    auto load_x = [&](int s, uint4 (&xr)[4]) {
+        const int64_t koff = (int64_t)(s < total_steps ? s : total_steps - 1) * WSTEP;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xr[i] = xok[i] ? *reinterpret_cast<const uint4*>(xp[i] + koff) : make_uint4(0, 0, 0, 0);
+    };
+    auto park_x = [&](int s, const uint4 (&xr)[4]) {
+        _Float16* const dst = As + (s & 1) * (WM * XLD);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 512 * i, row = idx >> 2, c = idx & 3;
+            *reinterpret_cast<uint4*>(&dst[row * XLD + c * 8]) = xr[i];
+        }
+    };
+    u32x4 t_lo;
+    u32x2 t_hi;
+    uint32_t t_sc;
+    auto load_tile = [&](int b) {
+        const int64_t tile = tile_base + (b < a.KB ? b : a.KB - 1);
+        const uint32_t* t = a.codes + tile * kTileWords;
+        t_lo = *reinterpret_cast<const u32x4*>(t + 4 * lane);
+        t_hi = *reinterpret_cast<const u32x2*>(t + kTileLoWords + 2 * lane);
+        t_sc = tile_ok ? a.scales[tile * kTileRows + r16] : 0u;
+    };
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     bool bad = false;
 
+    uint4 xr[2][4];  // activations of the next two steps on their way to LDS
+    load_tile(0);
+    load_x(0, xr[1]);
+    park_x(0, xr[1]);
+    load_x(1, xr[1]);
+
     for (int b = 0; b < a.KB; ++b) {
-        __syncthreads();  // the previous step's fragments have been read
-        // ---- activations: 128 rows x 256 channels, 16-byte pieces (row = idx/32, piece = idx%32)
-#pragma unroll 4
-        for (int i = 0; i < 16; ++i) {
-            const int idx = tid + 256 * i, row = idx >> 5, c = idx & 31;
-            const int64_t m = m0 + row;
-            const uint4 v = m < a.M ? *reinterpret_cast<const uint4*>(a.X + m * a.ldx + (int64_t)b * kBlock + c * 8) : make_uint4(0, 0, 0, 0);
-            *reinterpret_cast<uint4*>(&As[row * WLD + c * 8]) = v;
+        // ---- (1) reconstruct the wavefront's 16 rows of block b (everybody has left the previous block's products:
+        //          the barrier behind its last step)
+        *reinterpret_cast<u32x4*>(stage + 4 * lane) = t_lo;
+        *reinterpret_cast<u32x2*>(stage + kTileLoWords + 2 * lane) = t_hi;
+        if (lane < 16) {  // row r16's factors, once per tile: d / 16 (a power of two: commutes with every rounding) and 256 z
+            const float d16 = f16_bits_to_f32(t_sc & 0xffffu) * 0.0625f;
+            *reinterpret_cast<float2*>(stage + 384 + 2 * lane) = make_float2(d16, 256.0f * f16_bits_to_f32(t_sc >> 16));
         }
-        // ---- weights: wavefront w reconstructs rows 32w .. 32w+31 of the tile, one row per pass
+        bad |= tile_ok && (t_hi.x | t_hi.y) != 0u;
+        load_tile(b + 1);
 #pragma unroll 4
-        for (int rr = 0; rr < 32; ++rr) {
-            const int row = wave * 32 + rr;
-            const int64_t n = n0 + row;
-            half4 o = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
-            if (n < a.N) {  // wavefront-uniform
-                const int64_t tile = (n >> 4) * a.KB + b;
-                const int r = (int)(n & 15);
-                const uint32_t* t = a.codes + tile * kTileWords;
-                // channels e = 64 g + 16 j + r16 (j = 0..3) sit in slot r16 of low-plane word j of storage
-                // lane 16 g + r; their high bits in bit 16 (j & 1) + r16 of high-plane word j >> 1
-                const u32x4 lo = *reinterpret_cast<const u32x4*>(t + 4 * (16 * g + r));
-                const u32x2 hi = *reinterpret_cast<const u32x2*>(t + kTileLoWords + 2 * (16 * g + r));
-                const uint32_t sw = a.scales[tile * kTileRows + r];
-                const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w};
-                const uint32_t hw[2] = {hi.x, hi.y};
-                half4 v;
+        for (int rr = 0; rr < 16; ++rr) {
+            // channels e = 64 g + 16 j + r16 (j = 0..3) sit in slot r16 of low-plane word j of storage lane 16 g + rr
+            const u32x4 lo = *reinterpret_cast<const u32x4*>(stage + 4 * (16 * g + rr));
+            const float2 dz = *reinterpret_cast<const float2*>(stage + 384 + 2 * rr);
+            // two codes OR-ed into the mantissas of a pair of halves 1024.0, minus 1025: the digits c - 1, exact
+            const uint32_t p0 = ((lo.x >> (2 * r16)) & 3u) | (((lo.y >> (2 * r16)) & 3u) << 16) | 0x64006400u;
+            const uint32_t p1 = ((lo.z >> (2 * r16)) & 3u) | (((lo.w >> (2 * r16)) & 3u) << 16) | 0x64006400u;
+            const half2v bias = {(_Float16)(-1025.0f), (_Float16)(-1025.0f)};
+            const half2v v01 = __builtin_bit_cast(half2v, p0) + bias, v23 = __builtin_bit_cast(half2v, p1) + bias;
+            const half4 v = {v01[0], v01[1], v23[0], v23[1]};
+            const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+            const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(v, h, zero, 0, 0, 0);  // V^T H_16
+            const half4 th = {(_Float16)T[0], (_Float16)T[1], (_Float16)T[2], (_Float16)T[3]};
+            const floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);  // channels 16 r16 + 4 g + 0..3
+            const float f0 = lane == 0 ? U[0] - dz.y : U[0];  // H_u applied to the constant -z
+            const half4 o = {(_Float16)(dz.x * f0), (_Float16)(dz.x * U[1]), (_Float16)(dz.x * U[2]), (_Float16)(dz.x * U[3])};
+            *reinterpret_cast<half4*>(&Bs[(wave * 16 + rr) * WLD + 16 * r16 + 4 * g]) = o;
+        }
+        __syncthreads();  // the weight tile and the first step's activations are in place
+        // ---- (2) eight steps of 32 channels
+#pragma unroll 2
+        for (int e = 0; e < WK / WSTEP; ++e) {
+            const int s = b * (WK / WSTEP) + e;
+            load_x(s + 2, xr[e & 1]);  // two steps ahead: a step's products are shorter than a load's way from memory
+            const _Float16* const Ab = As + (s & 1) * (WM * XLD);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t c = (lw[j] >> (2 * r16)) & 3u;
-                    bad |= ((hw[j >> 1] >> (16 * (j & 1) + r16)) & 1u) != 0u;
-                    v[j] = (_Float16)(float)((int)c - 1);
-                }
-                const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
-                const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(v, h, zero, 0, 0, 0);  // V^T H_16
-                const half4 th = {(_Float16)T[0], (_Float16)T[1], (_Float16)T[2], (_Float16)T[3]};
-                const floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);  // channels 16 r16 + 4 g + 0..3
-                const float d = f16_bits_to_f32(sw & 0xffffu);
-                const float z = f16_bits_to_f32(sw >> 16);
-                float f[4] = {U[0], U[1], U[2], U[3]};
-                if (lane == 0) f[0] = f[0] - 256.0f * z;  // H_u applied to the constant -z
+            for (int ks = 0; ks < WSTEP / 16; ++ks) {
+                half8 af[4], bf[2];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (_Float16)((d * f[i]) * 0.0625f);
+                for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const half8*>(&Ab[(wm * 128 + i * 32 + l32) * XLD + ks * 16 + kg * 8]);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const half8*>(&Bs[(wn * 64 + j * 32 + l32) * WLD + e * WSTEP + ks * 16 + kg * 8]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
             }
-            *reinterpret_cast<half4*>(&Bs[row * WLD + 16 * r16 + 4 * g]) = o;
-        }
-        __syncthreads();
-        // ---- 16 MFMA steps over the block
-#pragma unroll 4
-        for (int ks = 0; ks < WK / 16; ++ks) {
-            half8 af[2], bf[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const half8*>(&As[(wm * 64 + i * 32 + l32) * WLD + ks * 16 + kg * 8]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const half8*>(&Bs[(wn * 64 + j * 32 + l32) * WLD + ks * 16 + kg * 8]);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
+            park_x(s + 1, xr[(e + 1) & 1]);  // the other buffer: its readers passed the barrier behind the previous step
+            __syncthreads();
         }
     }
 
     // accumulator register v of a 32x32 block: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int64_t n = n0 + wn * 64 + j * 32 + l32;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const int64_t m = m0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
                 if (m < a.M && n < a.N) {
                     if (a.y_f16) reinterpret_cast<_Float16*>(a.Y)[m * a.ldy + n] = (_Float16)acc[i][j][v];
                     else reinterpret_cast<float*>(a.Y)[m * a.ldy + n] = acc[i][j][v];
@@ -159,8 +210,8 @@ int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, int64
     }
     const dim3 grid((unsigned)((N + WN - 1) / WN), (unsigned)((M + WM - 1) / WM));
     const LaunchTiming tm = take_launch_timing();
-    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_ws_kernel, grid, dim3(256), kGemmWsLds, stream, tm.start, tm.stop, 0, a);
-    else hipLaunchKernelGGL(gemm_ws_kernel, grid, dim3(256), kGemmWsLds, stream, a);
+    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_ws_kernel, grid, dim3(512), kGemmWsLds, stream, tm.start, tm.stop, 0, a);
+    else hipLaunchKernelGGL(gemm_ws_kernel, grid, dim3(512), kGemmWsLds, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -718,7 +718,7 @@ def test_matmul_grouped_flags_and_determinism(gpu, ref):
             assert torch.equal(u, v)
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 48, 512), (17, 1000, 768), (130, 144, 2048), (300, 600, 1024), (512, 384, 4096)])
+@pytest.mark.parametrize("M,N,K", [(1, 48, 512), (17, 1000, 768), (130, 144, 2048), (300, 600, 1024), (512, 384, 4096), (700, 200, 512), (1030, 136, 768)])
 def test_matmul_weight_side_matches_oracle(gpu, ref, M, N, K):
     """The paper's placement of the transform (inside the weight tile loader): same product, same bar;
     zero-points over the whole range are exact here (they only touch channel 0 of a block)."""
@@ -764,6 +764,10 @@ def test_matmul_flags_high_plane(gpu, ref):
         binding.itq3s_matmul(to_dev(torch, bad.view(np.int32)), to_dev(torch, scales.view(np.int32)), 64, 512,
                              to_dev(torch, synth.activations(M, 512, "hp")), status_flags=flags)
         assert int(flags.item()) == binding.FLAG_BAD_CODE
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    binding.itq3s_matmul_weight_side(to_dev(torch, bad.view(np.int32)), to_dev(torch, scales.view(np.int32)), 64, 512,
+                                     to_dev(torch, synth.activations(32, 512, "hp")), status_flags=flags)
+    assert int(flags.item()) == binding.FLAG_BAD_CODE
 
 
 def sample_row_ranges(N, count, seed):
