@@ -163,7 +163,10 @@ __device__ __forceinline__ bool rotate_to_lds(u32x2 raw, const HadamardOperand& 
 // fragment fetched -- the bulk of what a workgroup pulls through its L1 with 16 rows -- serves twice
 // the weights, and its latency is met once per two steps.
 template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false, bool kRotated = false, int NSG = 1>
-__global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 2) void gemv_kernel(const GemvArgs a) {
+// (launch bounds: the second figure is a lower bound on wavefronts per SIMD: 4 = two workgroups per
+// compute unit = at most 128 registers, which every instantiation of the general pipeline meets
+// without scratch; the straight-line kernels use 57..92 registers on their own)
+__global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void gemv_kernel(const GemvArgs a) {
     static_assert(!kRotated || (NBC == 0 && !kSub && MP >= 8), "rotated activations: general pipeline, base format");
     static_assert(kRotated || MP <= 4, "in-kernel rotation: at most four rows");
     static_assert(NSG == 1 || (NSG == 2 && kRotated), "row sub-groups: with rotated activations only");
@@ -531,7 +534,6 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
     } else {
         int64_t want = (nt_total + cus - 1) / cus;
         if (want > kGemvMaxRT) want = kGemvMaxRT;
-        if (M == 2) want = 1;  // (two rows: more than one tile per workgroup would cost the second workgroup per unit)
         grid64 = (nt_total + want - 1) / want;
         if (grid64 < cus && nt_total >= cus) grid64 = cus;  // (workgroups then own `want` or `want - 1` tiles)
     }
