@@ -195,6 +195,14 @@ __global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void g
     // Per slot: descriptors over the K range of the tile row in codes / scales (scalar selects; all
     // tensor entries come with the first argument fetch).
     __amdgpu_buffer_rsrc_t crs[RTW], srs[RTW], urs[kSub ? RTW : 1];
+    void* so_y[RTW];  // the output table's entries: written behind the first loads, they are not needed before the end
+    int64_t so_ldy[RTW], so_n0[RTW], so_rows[RTW];
+    // grouped: the tensor of a slot is found from the three list positions alone, and its entry is then
+    // fetched from the argument block by index (one scalar load per slot, all in flight together) --
+    // selecting every field among four entries took 340 scalar instructions and nine dependent fetches
+    // in front of the first weight load
+    [[maybe_unused]] const auto* const kargs = (const __attribute__((address_space(4))) GemvArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+    [[maybe_unused]] const int vb1 = a.t[1].v_begin, vb2 = a.t[2].v_begin, vb3 = a.t[3].v_begin;
 #pragma unroll
     for (int rt = 0; rt < RTW; ++rt) {
         const uint32_t* t_codes = a.t[0].codes;
@@ -203,16 +211,14 @@ __global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void g
         int64_t t_n = a.t[0].N, t_ldy = a.t[0].ldy;
         int t_begin = 0;
         if constexpr (kGrouped) {
-#pragma unroll
-            for (int i = 1; i < kGemvMaxGroup; ++i) {
-                const bool ge = nt_begin + rt >= a.t[i].v_begin;
-                t_codes = ge ? a.t[i].codes : t_codes;
-                t_scales = ge ? a.t[i].scales : t_scales;
-                t_y = ge ? a.t[i].Y : t_y;
-                t_n = ge ? a.t[i].N : t_n;
-                t_ldy = ge ? a.t[i].ldy : t_ldy;
-                t_begin = ge ? a.t[i].v_begin : t_begin;
-            }
+            const int tile = nt_begin + rt;
+            const int ti = (tile >= vb1 ? 1 : 0) + (tile >= vb2 ? 1 : 0) + (tile >= vb3 ? 1 : 0);  // list positions ascend; unused entries hold INT_MAX
+            t_codes = kargs->t[ti].codes;
+            t_scales = kargs->t[ti].scales;
+            t_y = kargs->t[ti].Y;
+            t_n = kargs->t[ti].N;
+            t_ldy = kargs->t[ti].ldy;
+            t_begin = kargs->t[ti].v_begin;
         }
         const bool have = rt < cnt;
         const int64_t local = nt_begin + rt - t_begin;
@@ -220,7 +226,10 @@ __global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void g
         crs[rt] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(t_codes + first * kTileWords), 0, have ? KB * 1536 : 0, kRawBuffer);
         srs[rt] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(t_scales + first * kTileRows), 0, have ? KB * 64 : 0, kRawBuffer);
         if constexpr (kSub) urs[rt] = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(a.t[0].subscales + first * 64), 0, have ? KB * 256 : 0, kRawBuffer);
-        if (threadIdx.x == 0) slot_out[rt] = SlotOut{t_y, t_ldy, local * 16, have ? t_n - local * 16 : 0};
+        so_y[rt] = t_y;
+        so_ldy[rt] = t_ldy;
+        so_n0[rt] = local * 16;
+        so_rows[rt] = have ? t_n - local * 16 : 0;
     }
     // activations: rows beyond M read as zeros (offset outside the descriptor's range)
     const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
@@ -354,6 +363,11 @@ __global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void g
     // barriers keep the loads in front of the arithmetic they overlap with)
     issue(ring[0], 0);
     if constexpr (kRotated) issue_x(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt) slot_out[rt] = SlotOut{so_y[rt], so_ldy[rt], so_n0[rt], so_rows[rt]};
+    }
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (NBC > 0) {
 #pragma unroll
