@@ -199,8 +199,10 @@ int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block
  *   subscales: NT*KB*64 uint32 (itq3s_subscales_bytes), 16-byte aligned; word (nt*KB + b)*64 + 16 g + r =
  *     fp16 s_(2g) | fp16 s_(2g+1) << 16 for tile row r and quarter g of the block (0 for rows >= N).
  * Other arguments, flags and errors as for itq3s_quantize / itq3s_dequantize / itq3s_matmul.
- * itq3s_matmul_sub needs no workspace: it runs ceil(M/4) passes of the streaming kernel (the variant
- * has no tiled path).  It multiplies with the sub-scales in fp16: exact for 1/16 <= s_j <= 4094 (the
+ * itq3s_matmul_sub needs no workspace: up to M = 64 it runs ceil(M/4) passes of the streaming kernel,
+ * above that the tiled kernel that reconstructs weight tiles on chip (the placement of
+ * itq3s_matmul_weight_side; one pass over the weights per 512 rows, ceil(M/512) <= 65535).  The
+ * streaming kernel multiplies with the sub-scales in fp16: exact for 1/16 <= s_j <= 4094 (the
  * quantizer's values lie below 3); smaller ones lose low bits of a small contribution, larger ones
  * are not supported. */
 size_t itq3s_subscales_bytes(int64_t N, int64_t K);

@@ -48,6 +48,7 @@ struct WorkspacePlan {
 
 // N = the largest tensor of the call (sizes the split-K shares of the tiled path)
 constexpr int64_t kChunkedMaxM = 2 * itq3s::kGemvMaxM;  // up to here M > 16 runs as passes of the streaming kernel
+constexpr int64_t kSubStreamingMaxM = 64;               // sub-block variant: up to here passes of four rows, the tiled weight-side kernel above
 
 WorkspacePlan plan_workspace(int64_t M, int64_t N, int64_t K) {
     if (M > itq3s::kGemvMaxM && M <= kChunkedMaxM) return plan_workspace(itq3s::kGemvMaxM, N, K);
@@ -261,6 +262,12 @@ int itq3s_matmul_sub(const uint32_t* codes, const uint32_t* scales, const uint32
     if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(subscales, 16) ||
         !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) || (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
+    // many rows: the tiled kernel that reconstructs weight tiles on chip (one pass over the weights per 512 rows)
+    if (M > kSubStreamingMaxM) {
+        if ((M + 511) / 512 > 65535) return ITQ3S_ERR_SHAPE;
+        return itq3s::launch_gemm_weight_side(codes, scales, subscales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy,
+                                              status_flags, static_cast<hipStream_t>(stream));
+    }
     // up to four rows per pass of the streaming kernel (it rotates the activations itself)
     const size_t y_bytes = y_dtype == ITQ3S_F16 ? 2 : 4;
     for (int64_t m0 = 0; m0 < M; m0 += itq3s::kGemvFusedMaxM) {
@@ -292,7 +299,7 @@ int itq3s_matmul_weight_side(const uint32_t* codes, const uint32_t* scales, int6
     if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) ||
         (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
-    return itq3s::launch_gemm_weight_side(codes, scales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags,
+    return itq3s::launch_gemm_weight_side(codes, scales, nullptr, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy, status_flags,
                                           static_cast<hipStream_t>(stream));
 }
 

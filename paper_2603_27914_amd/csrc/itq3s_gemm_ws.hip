@@ -37,14 +37,15 @@ namespace itq3s {
 constexpr int WM = 512, WN = 128, WK = 256, WSTEP = 32;
 constexpr int WLD = WK + 8;                   // weight tile row stride in halves (528 bytes: 16-byte reads conflict-free)
 constexpr int XLD = WSTEP + 8;                // activation buffer row stride in halves (80 bytes)
-constexpr int kWsStageWords = 416;            // per wavefront: 256 low-plane + 128 high-plane words, 16 x (d / 16, 256 z) as floats
+constexpr int kWsStageWords = 352;            // per wavefront: 256 low-plane words, 16 x (d / 16, 256 z) as floats, 64 sub-scale words
 constexpr int kWsBsBytes = WN * WLD * 2;      // 67584
 constexpr int kWsAsBytes = WM * XLD * 2;      // 40960 per buffer
-constexpr int kGemmWsLds = kWsBsBytes + 2 * kWsAsBytes + 8 * kWsStageWords * 4;  // 162816 of 163840
+constexpr int kGemmWsLds = kWsBsBytes + 2 * kWsAsBytes + 8 * kWsStageWords * 4;  // 160768 of 163840
 
 struct GemmWsArgs {
     const uint32_t* codes;
     const uint32_t* scales;
+    const uint32_t* subscales;  // the 116-byte variant's sub-scale array (kSub)
     const _Float16* X;  // [M][ldx], not rotated
     void* Y;
     uint32_t* flags;
@@ -52,6 +53,11 @@ struct GemmWsArgs {
     int NT, KB, y_f16;
 };
 
+// kSub: the sub-block-scale variant (Sec. 4.1): the digit of channel j of the rotated block is multiplied by
+// the fp16 scale of its sub-block (j / 32) before the transform; the products are exact halves, their
+// 16-term sums T are not, so T goes into the second product as two halves (22 bits) and that product
+// takes two matrix instructions instead of one.
+template <bool kSub>
 __global__ __launch_bounds__(512) void gemm_ws_kernel(const GemmWsArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     _Float16* const Bs = reinterpret_cast<_Float16*>(lds_raw);                       // [WN][WLD] reconstructed weights of the block
@@ -102,13 +108,14 @@ __global__ __launch_bounds__(512) void gemm_ws_kernel(const GemmWsArgs a) {
     };
     u32x4 t_lo;
     u32x2 t_hi;
-    uint32_t t_sc;
+    uint32_t t_sc, t_ss = 0u;
     auto load_tile = [&](int b) {
         const int64_t tile = tile_base + (b < a.KB ? b : a.KB - 1);
         const uint32_t* t = a.codes + tile * kTileWords;
         t_lo = *reinterpret_cast<const u32x4*>(t + 4 * lane);
         t_hi = *reinterpret_cast<const u32x2*>(t + kTileLoWords + 2 * lane);
         t_sc = tile_ok ? a.scales[tile * kTileRows + r16] : 0u;
+        if constexpr (kSub) t_ss = a.subscales[tile * 64 + lane];
     };
 
     floatx16 acc[4][2];
@@ -130,28 +137,36 @@ __global__ __launch_bounds__(512) void gemm_ws_kernel(const GemmWsArgs a) {
         // ---- (1) reconstruct the wavefront's 16 rows of block b (everybody has left the previous block's products:
         //          the barrier behind its last step)
         *reinterpret_cast<u32x4*>(stage + 4 * lane) = t_lo;
-        *reinterpret_cast<u32x2*>(stage + kTileLoWords + 2 * lane) = t_hi;
         if (lane < 16) {  // row r16's factors, once per tile: d / 16 (a power of two: commutes with every rounding) and 256 z
             const float d16 = f16_bits_to_f32(t_sc & 0xffffu) * 0.0625f;
-            *reinterpret_cast<float2*>(stage + 384 + 2 * lane) = make_float2(d16, 256.0f * f16_bits_to_f32(t_sc >> 16));
+            *reinterpret_cast<float2*>(stage + 256 + 2 * lane) = make_float2(d16, 256.0f * f16_bits_to_f32(t_sc >> 16));
         }
+        if constexpr (kSub) stage[288 + lane] = t_ss;
         bad |= tile_ok && (t_hi.x | t_hi.y) != 0u;
         load_tile(b + 1);
 #pragma unroll 4
         for (int rr = 0; rr < 16; ++rr) {
             // channels e = 64 g + 16 j + r16 (j = 0..3) sit in slot r16 of low-plane word j of storage lane 16 g + rr
             const u32x4 lo = *reinterpret_cast<const u32x4*>(stage + 4 * (16 * g + rr));
-            const float2 dz = *reinterpret_cast<const float2*>(stage + 384 + 2 * rr);
+            const float2 dz = *reinterpret_cast<const float2*>(stage + 256 + 2 * rr);
             // two codes OR-ed into the mantissas of a pair of halves 1024.0, minus 1025: the digits c - 1, exact
             const uint32_t p0 = ((lo.x >> (2 * r16)) & 3u) | (((lo.y >> (2 * r16)) & 3u) << 16) | 0x64006400u;
             const uint32_t p1 = ((lo.z >> (2 * r16)) & 3u) | (((lo.w >> (2 * r16)) & 3u) << 16) | 0x64006400u;
             const half2v bias = {(_Float16)(-1025.0f), (_Float16)(-1025.0f)};
             const half2v v01 = __builtin_bit_cast(half2v, p0) + bias, v23 = __builtin_bit_cast(half2v, p1) + bias;
-            const half4 v = {v01[0], v01[1], v23[0], v23[1]};
+            half4 v = {v01[0], v01[1], v23[0], v23[1]};
+            if constexpr (kSub) {  // channels 64 g + 16 j + r16: sub-block 2 g for j = 0, 1 and 2 g + 1 for j = 2, 3 (the two halves of the lane's word)
+                const half2v s2 = __builtin_bit_cast(half2v, stage[288 + 16 * g + rr]);
+                v = half4{v[0] * s2[0], v[1] * s2[0], v[2] * s2[1], v[3] * s2[1]};
+            }
             const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
             const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(v, h, zero, 0, 0, 0);  // V^T H_16
             const half4 th = {(_Float16)T[0], (_Float16)T[1], (_Float16)T[2], (_Float16)T[3]};
-            const floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);  // channels 16 r16 + 4 g + 0..3
+            floatx4 U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, th, zero, 0, 0, 0);  // channels 16 r16 + 4 g + 0..3
+            if constexpr (kSub) {
+                const half4 tl = {(_Float16)(T[0] - (float)th[0]), (_Float16)(T[1] - (float)th[1]), (_Float16)(T[2] - (float)th[2]), (_Float16)(T[3] - (float)th[3])};
+                U = __builtin_amdgcn_mfma_f32_16x16x16f16(h, tl, U, 0, 0, 0);
+            }
             const float f0 = lane == 0 ? U[0] - dz.y : U[0];  // H_u applied to the constant -z
             const half4 o = {(_Float16)(dz.x * f0), (_Float16)(dz.x * U[1]), (_Float16)(dz.x * U[2]), (_Float16)(dz.x * U[3])};
             *reinterpret_cast<half4*>(&Bs[(wave * 16 + rr) * WLD + 16 * r16 + 4 * g]) = o;
@@ -198,21 +213,26 @@ __global__ __launch_bounds__(512) void gemm_ws_kernel(const GemmWsArgs a) {
     if (a.flags != nullptr && __builtin_amdgcn_ballot_w64(bad) != 0ull && lane == 0) atomicOr(a.flags, kFlagBadCode);
 }
 
-int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, int64_t M,
-                            void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
-    GemmWsArgs a;
-    a.codes = codes; a.scales = scales; a.X = X; a.Y = Y; a.flags = flags;
-    a.N = N; a.M = M; a.ldx = ldx; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
+template <bool kSub>
+static int launch_ws(const GemmWsArgs& a, dim3 grid, hipStream_t stream) {
     static std::atomic<bool> lds_limit_raised{false};
     if (!lds_limit_raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ws_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmWsLds) != hipSuccess) return -6;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ws_kernel<kSub>), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmWsLds) != hipSuccess) return -6;
         lds_limit_raised = true;
     }
-    const dim3 grid((unsigned)((N + WN - 1) / WN), (unsigned)((M + WM - 1) / WM));
     const LaunchTiming tm = take_launch_timing();
-    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_ws_kernel, grid, dim3(512), kGemmWsLds, stream, tm.start, tm.stop, 0, a);
-    else hipLaunchKernelGGL(gemm_ws_kernel, grid, dim3(512), kGemmWsLds, stream, a);
+    if (tm.start != nullptr) hipExtLaunchKernelGGL(gemm_ws_kernel<kSub>, grid, dim3(512), kGemmWsLds, stream, tm.start, tm.stop, 0, a);
+    else hipLaunchKernelGGL(gemm_ws_kernel<kSub>, grid, dim3(512), kGemmWsLds, stream, a);
     return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, const _Float16* X,
+                            int64_t ldx, int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream) {
+    GemmWsArgs a;
+    a.codes = codes; a.scales = scales; a.subscales = subscales; a.X = X; a.Y = Y; a.flags = flags;
+    a.N = N; a.M = M; a.ldx = ldx; a.ldy = ldy; a.NT = (int)((N + 15) / 16); a.KB = (int)(K / kBlock); a.y_f16 = y_f16;
+    const dim3 grid((unsigned)((N + WN - 1) / WN), (unsigned)((M + WM - 1) / WM));
+    return subscales != nullptr ? launch_ws<true>(a, grid, stream) : launch_ws<false>(a, grid, stream);
 }
 
 }  // namespace itq3s

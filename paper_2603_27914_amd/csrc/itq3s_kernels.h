@@ -83,9 +83,9 @@ int launch_gemm(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_
                 hipStream_t stream);
 
 // Tiled matmul with the inverse transform applied to the weights inside the tile loader (Alg. 2 as
-// printed); X = the activations themselves.  Any M.
-int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, int64_t N, int64_t K, const _Float16* X, int64_t ldx, int64_t M,
-                            void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
+// printed); X = the activations themselves.  Any M.  subscales: the 116-byte variant's array, or null.
+int launch_gemm_weight_side(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, const _Float16* X,
+                            int64_t ldx, int64_t M, void* Y, int y_f16, int64_t ldy, uint32_t* flags, hipStream_t stream);
 
 // Round trip with transform length n in {32 .. 512} (block-size ablation, Sec. 6); any of codes,
 // scales, What, err may be null.  Returns -2 for another n.

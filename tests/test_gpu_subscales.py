@@ -131,6 +131,27 @@ def test_matmul_sub(gpu, ref, M, N, K):
         assert rel_rows(a, ref.matmul(rc, rs, N, K, X)) <= 2e-3
 
 
+@pytest.mark.parametrize("M,N,K", [(65, 48, 512), (130, 1000, 768), (600, 200, 512), (1030, 136, 1024)])
+def test_matmul_sub_many_rows(gpu, ref, M, N, K):
+    """Above 64 rows the product runs on the tiled kernel that reconstructs weight tiles on chip (sub-scaled
+    digits through the inverse transform, one rounding of w_hat to fp16): same bar; one and several
+    512-row slabs, row tiles beyond the tensor, and the base format's product for sub-scales 1."""
+    torch, binding = gpu
+    W = uneven_weights(N, K, "mm-rows", N)
+    rc, rs, rsub, _ = ref.quantize_sub(W)
+    cd, sd, ud = dev(torch, rc.view(np.int32)), dev(torch, rs.view(np.int32)), dev(torch, rsub.view(np.int32))
+    X = synth.activations(M, K, "sub-rows", M, N)
+    want = ref.matmul_sub(rc, rs, rsub, N, K, X)
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for dtype in (torch.float32, torch.float16):
+        got = binding.itq3s_matmul_sub(cd, sd, ud, N, K, dev(torch, X), dtype=dtype, status_flags=flags).float().cpu().numpy()
+        assert rel_rows(got, want) <= 2e-3
+    assert int(flags.item()) == 0
+    ones = torch.full_like(ud, 0x3C003C00)
+    a = binding.itq3s_matmul_sub(cd, sd, ones, N, K, dev(torch, X)).cpu().numpy()
+    assert rel_rows(a, ref.matmul(rc, rs, N, K, X)) <= 2e-3
+
+
 def test_matmul_sub_full_size_sampled(gpu, ref):
     """A 70B-shaped tensor in the launch configuration a decode step uses, checked on sampled rows."""
     torch, binding = gpu
