@@ -199,9 +199,11 @@ int itq3s_roundtrip(const float *W, int64_t N, int64_t K, int64_t ldw, int block
  *   subscales: NT*KB*64 uint32 (itq3s_subscales_bytes), 16-byte aligned; word (nt*KB + b)*64 + 16 g + r =
  *     fp16 s_(2g) | fp16 s_(2g+1) << 16 for tile row r and quarter g of the block (0 for rows >= N).
  * Other arguments, flags and errors as for itq3s_quantize / itq3s_dequantize / itq3s_matmul.
- * itq3s_matmul_sub needs no workspace: up to M = 64 it runs ceil(M/4) passes of the streaming kernel,
- * above that the tiled kernel that reconstructs weight tiles on chip (the placement of
- * itq3s_matmul_weight_side; one pass over the weights per 512 rows, ceil(M/512) <= 65535).  The
+ * itq3s_matmul_sub: up to M = 64 it runs ceil(M/16) passes of the streaming kernel, above that the
+ * tiled kernel that reconstructs weight tiles on chip (the placement of itq3s_matmul_weight_side; one
+ * pass over the weights per 512 rows, ceil(M/512) <= 65535).  workspace: for 5 <= M <= 64 at least
+ * itq3s_matmul_workspace_bytes(min(M, 16), N, K) bytes, 256-byte aligned (the rotated activations of a
+ * pass), else ITQ3S_ERR_WORKSPACE; not used for other M (may be NULL).  The
  * streaming kernel multiplies with the sub-scales in fp16: exact for 1/16 <= s_j <= 4094 (the
  * quantizer's values lie below 3); smaller ones lose low bits of a small contribution, larger ones
  * are not supported. */
@@ -211,8 +213,8 @@ int itq3s_quantize_sub(const float *W, int64_t N, int64_t K, int64_t ldw, uint32
 int itq3s_dequantize_sub(const uint32_t *codes, const uint32_t *scales, const uint32_t *subscales, int64_t N, int64_t K,
                          void *W_out, int out_dtype, int64_t ldo, uint32_t *status_flags, void *stream);
 int itq3s_matmul_sub(const uint32_t *codes, const uint32_t *scales, const uint32_t *subscales, int64_t N, int64_t K,
-                     const void *X, int64_t M, int64_t ldx, void *Y, int y_dtype, int64_t ldy, uint32_t *status_flags,
-                     void *stream);
+                     const void *X, int64_t M, int64_t ldx, void *Y, int y_dtype, int64_t ldy, void *workspace,
+                     size_t workspace_bytes, uint32_t *status_flags, void *stream);
 
 /* Static text for a status code.  Never NULL. */
 const char *itq3s_strerror(int status);

@@ -83,7 +83,7 @@ def lib():
         L.itq3s_dequantize_sub.restype = ci
         L.itq3s_dequantize_sub.argtypes = [vp, vp, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul_sub.restype = ci
-        L.itq3s_matmul_sub.argtypes = [vp, vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp]
+        L.itq3s_matmul_sub.argtypes = [vp, vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, sz, vp, vp]
         L.itq3s_matmul_static.restype = ci
         L.itq3s_matmul_static.argtypes = [vp, vp, i64, i64, vp, i64, i64, vp, ci, i64, vp, vp]
         L.itq3s_matmul_grouped.restype = ci
@@ -405,9 +405,11 @@ def itq3s_dequantize_sub(codes, scales, subscales, N, K, dtype=torch.float32, st
     return out
 
 
-def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, status_flags=None):
-    """Y[M, N] = X[M, K] @ W_hat[N, K]^T from weights packed in the sub-block-scale variant."""
-    _need_cuda(codes, scales, subscales, X, status_flags)
+def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, workspace=None, status_flags=None):
+    """Y[M, N] = X[M, K] @ W_hat[N, K]^T from weights packed in the sub-block-scale variant.
+    workspace: uint8 tensor of itq3s_matmul_workspace_bytes(min(M, 16), N, K) bytes for 5 <= M <= 64
+    (allocated here if not given)."""
+    _need_cuda(codes, scales, subscales, X, status_flags, workspace)
     _need_packed(codes, scales, N, K, subscales, X, status_flags)
     _need_subscales(subscales, codes, N, K)
     _need_flags(status_flags)
@@ -416,7 +418,11 @@ def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, sta
     if dtype not in (torch.float32, torch.float16):
         raise Itq3sError("dtype must be float32 or float16")
     M = X.shape[0]
+    if workspace is None and 4 < M <= 64:
+        workspace = torch.empty(itq3s_matmul_workspace_bytes(min(M, 16), N, K), dtype=torch.uint8, device=X.device)
+    if workspace is not None and (workspace.dtype != torch.uint8 or not workspace.is_contiguous()):
+        raise Itq3sError("workspace must be a contiguous uint8 tensor")
     out = torch.empty((M, N), dtype=dtype, device=X.device)
     _check(lib().itq3s_matmul_sub(_ptr(codes), _ptr(scales), _ptr(subscales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if dtype == torch.float16 else F32,
-                                  out.stride(0), _ptr(status_flags), _stream()))
+                                  out.stride(0), _ptr(workspace), workspace.numel() if workspace is not None else 0, _ptr(status_flags), _stream()))
     return out

@@ -254,7 +254,7 @@ int itq3s_dequantize_sub(const uint32_t* codes, const uint32_t* scales, const ui
 }
 
 int itq3s_matmul_sub(const uint32_t* codes, const uint32_t* scales, const uint32_t* subscales, int64_t N, int64_t K, const void* X, int64_t M,
-                     int64_t ldx, void* Y, int y_dtype, int64_t ldy, uint32_t* status_flags, void* stream) {
+                     int64_t ldx, void* Y, int y_dtype, int64_t ldy, void* workspace, size_t workspace_bytes, uint32_t* status_flags, void* stream) {
     if (!codes || !scales || !subscales || !X || !Y) return ITQ3S_ERR_NULL;
     if (N <= 0 || K <= 0 || M <= 0 || K % 256 != 0 || ldx < K || ldy < N) return ITQ3S_ERR_SHAPE;
     if (K > (1LL << 28) || 3 * ldx + K > (1LL << 29) || (N + 15) / 16 > 0x7fffffffLL / (K / 256)) return ITQ3S_ERR_SHAPE;
@@ -262,19 +262,35 @@ int itq3s_matmul_sub(const uint32_t* codes, const uint32_t* scales, const uint32
     if (!aligned(X, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(scales, 16) || !aligned(subscales, 16) ||
         !aligned(Y, y_dtype == ITQ3S_F16 ? 2 : 4) || (status_flags && !aligned(status_flags, 4)))
         return ITQ3S_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int y_f16 = y_dtype == ITQ3S_F16;
     // many rows: the tiled kernel that reconstructs weight tiles on chip (one pass over the weights per 512 rows)
     if (M > kSubStreamingMaxM) {
         if ((M + 511) / 512 > 65535) return ITQ3S_ERR_SHAPE;
-        return itq3s::launch_gemm_weight_side(codes, scales, subscales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_dtype == ITQ3S_F16, ldy,
-                                              status_flags, static_cast<hipStream_t>(stream));
+        return itq3s::launch_gemm_weight_side(codes, scales, subscales, N, K, static_cast<const _Float16*>(X), ldx, M, Y, y_f16, ldy, status_flags, st);
     }
-    // up to four rows per pass of the streaming kernel (it rotates the activations itself)
-    const size_t y_bytes = y_dtype == ITQ3S_F16 ? 2 : 4;
-    for (int64_t m0 = 0; m0 < M; m0 += itq3s::kGemvFusedMaxM) {
-        const int64_t rows = M - m0 < itq3s::kGemvFusedMaxM ? M - m0 : itq3s::kGemvFusedMaxM;
+    // the streaming kernel: passes of up to 16 rows; a pass of up to four rows rotates the activations
+    // itself, a longer one takes them from a rotation launch through the workspace
+    const WorkspacePlan p = plan_workspace(M < itq3s::kGemvMaxM ? M : itq3s::kGemvMaxM, N, K);
+    if (M > itq3s::kGemvFusedMaxM) {
+        if (!workspace || workspace_bytes < p.total) return ITQ3S_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return ITQ3S_ERR_ALIGN;
+    }
+    const size_t y_bytes = y_f16 ? 2 : 4;
+    for (int64_t m0 = 0; m0 < M; m0 += itq3s::kGemvMaxM) {
+        const int64_t rows = M - m0 < itq3s::kGemvMaxM ? M - m0 : itq3s::kGemvMaxM;
+        const _Float16* Xh = static_cast<const _Float16*>(X) + m0 * ldx;
         itq3s::GemvWeight gw{codes, scales, N, static_cast<unsigned char*>(Y) + (size_t)m0 * (size_t)ldy * y_bytes, ldy, subscales};
-        const int rc = itq3s::launch_gemv(&gw, 1, K, static_cast<const _Float16*>(X) + m0 * ldx, ldx, rows, y_dtype == ITQ3S_F16, status_flags,
-                                          static_cast<hipStream_t>(stream));
+        int rc;
+        if (rows <= itq3s::kGemvFusedMaxM) {
+            rc = itq3s::launch_gemv(&gw, 1, K, Xh, ldx, rows, y_f16, status_flags, st);
+        } else {
+            const int MP = pad_m(rows) < 8 ? 8 : pad_m(rows);
+            _Float16* Xt = static_cast<_Float16*>(workspace);
+            float* S = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.xt_bytes);
+            rc = itq3s::launch_rotate_frag(Xh, rows, K, ldx, MP, Xt, S, status_flags, st);
+            if (rc == 0) rc = itq3s::launch_gemv_rows(&gw, 1, K, Xt, S, rows, MP, y_f16, status_flags, st);
+        }
         if (rc != 0) return rc;
     }
     return ITQ3S_OK;

@@ -153,7 +153,7 @@ __device__ __forceinline__ bool rotate_to_lds(u32x2 raw, const HadamardOperand& 
 // (c 2^-14) (16 s) - s 2^-10 = (c-1) s 2^-10, exact in fp16 for 2^-4 <= s <= 4094 (the quantizer's
 // sub-scales lie below 3; smaller ones lose low bits of a contribution that is small anyway), so no
 // block sum S is needed.
-// kRotated (5..16 rows, MP = 8 or 16): the activations arrive rotated, in operand order, from a launch
+// kRotated (5..16 rows, MP = 8 or 16; either format): the activations arrive rotated, in operand order, from a launch
 // of their own (rotating 8 or 16 rows per block inside every workgroup would cost more than the
 // contraction); a wavefront loads the eight fragments and the two sums of its next block straight into
 // registers right behind the arithmetic of the current one, in front of the next tile loads, so that
@@ -166,8 +166,8 @@ template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false, bool kRotat
 // (launch bounds: the second figure is a lower bound on wavefronts per SIMD: 4 = two workgroups per
 // compute unit = at most 128 registers, which every instantiation of the general pipeline meets
 // without scratch; the straight-line kernels use 57..92 registers on their own)
-__global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void gemv_kernel(const GemvArgs a) {
-    static_assert(!kRotated || (NBC == 0 && !kSub && MP >= 8), "rotated activations: general pipeline, base format");
+__global__ __launch_bounds__(kGemvWaves * 64, (kSub && !kRotated) ? 2 : NBC > 0 ? 3 : 4) void gemv_kernel(const GemvArgs a) {
+    static_assert(!kRotated || (NBC == 0 && MP >= 8), "rotated activations: general pipeline");
     static_assert(kRotated || MP <= 4, "in-kernel rotation: at most four rows");
     static_assert(NSG == 1 || (NSG == 2 && kRotated), "row sub-groups: with rotated activations only");
     constexpr int RTW = RT * NSG;  // row tiles of the workgroup
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(kGemvWaves * 64, kSub ? 2 : NBC > 0 ? 3 : 4) void g
             s.t[rt].lo = __builtin_amdgcn_raw_buffer_load_b128(crs[SG * RT + rt], off_lo, b * 1536, kLoadNT);
             s.t[rt].hi = __builtin_amdgcn_raw_buffer_load_b64(crs[SG * RT + rt], off_hi, b * 1536, kLoadNT);
             s.t[rt].sc = __builtin_amdgcn_raw_buffer_load_b32(srs[SG * RT + rt], off_sc, b * 64, kLoadNT);
-            if constexpr (kSub) s.t[rt].ss = __builtin_amdgcn_raw_buffer_load_b32(urs[rt], off_ss, b * 256, kLoadNT);
+            if constexpr (kSub) s.t[rt].ss = __builtin_amdgcn_raw_buffer_load_b32(urs[SG * RT + rt], off_ss, b * 256, kLoadNT);
         }
     };
     auto issue = [&](Slot& s, int j) { issue_sg(s, j, std::integral_constant<int, 0>{}); };
@@ -566,6 +566,14 @@ int launch_gemv(const GemvWeight* w, int count, int64_t K, const _Float16* X, in
 template <int MP>
 static int launch_rotated(const GemvArgs& a, int grid, int rt, hipStream_t stream) {
     const bool grouped = a.t[1].v_begin != 0x7fffffff;
+    if (a.t[0].subscales != nullptr) {  // the sub-block variant: one tensor per launch
+        switch (rt) {
+            case 1: return launch_kernel<MP, 1, false, 0, true, true>(a, grid, stream);
+            case 2: return launch_kernel<MP, 2, false, 0, true, true>(a, grid, stream);
+            case 3: case 4: return launch_kernel<MP, 2, false, 0, true, true, 2>(a, grid, stream);
+        }
+        return -2;
+    }
     switch (rt) {
         case 1: return grouped ? launch_kernel<MP, 1, true, 0, false, true>(a, grid, stream) : launch_kernel<MP, 1, false, 0, false, true>(a, grid, stream);
         case 2: return grouped ? launch_kernel<MP, 2, true, 0, false, true>(a, grid, stream) : launch_kernel<MP, 2, false, 0, false, true>(a, grid, stream);

@@ -111,8 +111,8 @@ def test_dequantize_sub(gpu, ref, N, K):
     assert torch.equal(binding.itq3s_dequantize_sub(cd, sd, ones, N, K), binding.itq3s_dequantize(cd, sd, N, K))
 
 
-@pytest.mark.parametrize("M", [1, 2, 3, 4, 7, 20])
-@pytest.mark.parametrize("N,K", [(48, 512), (1000, 1024), (1160, 4096), (272, 11008)])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 7, 16, 20, 37, 64])  # fused rotation; rotation launch (8 and 16 padded rows); several passes
+@pytest.mark.parametrize("N,K", [(48, 512), (1000, 1024), (1160, 4096), (272, 11008), (9000, 512)])
 def test_matmul_sub(gpu, ref, M, N, K):
     torch, binding = gpu
     W = uneven_weights(N, K, "mm", N)
@@ -184,4 +184,7 @@ def test_sub_rejects_bad_arguments(gpu):
         binding.itq3s_matmul_sub(codes, scales, subs[:-1], N, K, X)
     with pytest.raises(binding.Itq3sError, match="subscales"):
         binding.itq3s_dequantize_sub(codes, scales, subs.float(), N, K)
+    X8 = torch.zeros((8, K), dtype=torch.float16, device="cuda")
+    with pytest.raises(binding.Itq3sError, match="workspace"):
+        binding.itq3s_matmul_sub(codes, scales, subs, N, K, X8, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert binding.itq3s_subscales_bytes(N, K) == 2 * 2 * 256 and binding.itq3s_subscales_bytes(N, 500) == 0
