@@ -138,7 +138,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="only the timed step and the roofline pass")
     ap.add_argument("--ungrouped", action="store_true", help="one library call (one launch) per tensor instead of one per stage")
     ap.add_argument("--prefill-m", default="512,2048", help="activation row counts of the prefill leg")
-    ap.add_argument("--legs", default="single,per_shape,stream7b,read_floor,prefill,dequantize,ablation,copy,cpu", help="comma list of the extra legs to run")
+    ap.add_argument("--legs", default="single,per_shape,stream7b,read_floor,prefill,dequantize,sub,ablation,copy,cpu", help="comma list of the extra legs to run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -285,6 +285,8 @@ def main():
                                 "unit": "TFLOP/s", "frac": round(best["kernel_TFLOPs"] / MFMA_F16_PEAK_TFLOPS, 4),
                                 "workload": "X fp16 [%d, %d] x ITQ3_S W %dx%d, fp16 out" % (best["M"], best["K"], best["N"], best["K"]),
                                 "whole_call_TFLOPs": best["TFLOPs"], "whole_call_frac": best["frac_of_mfma_peak"]}
+    if "sub" in legs:
+        out["sub_block_variant"] = sub_variant_leg(torch, binding, gen)
     if "ablation" in legs:
         out["block_size_ablation"] = ablation_leg(torch, binding, gen)
     if "copy" in legs:
@@ -372,6 +374,38 @@ def per_shape_leg(torch, binding, tensors, gen, Ms, out_dtype):
             res.append({"N": N, "K": K, "M": M, "out": str(out_dtype).replace("torch.", ""), "us": round(ms * 1e3, 2),
                         "GBps": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(packed_bytes(N, K) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                         "copies": len(same)})
+    return res
+
+
+def sub_variant_leg(torch, binding, gen, N=28672, K=8192, copies=8):
+    """The 116-byte sub-block-scale variant of the format (Sec. 4.1) on the largest tensor shape:
+    itq3s_quantize_sub (fp32 in), then itq3s_matmul_sub for M = 1, 4, 16 and 512 as a replayed graph
+    cycling through `copies` packed copies (0.85 GB: weights come from HBM).  Bytes per block: 116."""
+    nb = ((N + 15) // 16) * 16 * (K // 256)
+    packed = nb * 116
+    W = student_t_weights(torch, gen, N, K)
+    first = binding.itq3s_quantize_sub(W)
+    q_ms = time_calls(torch, lambda: binding.itq3s_quantize_sub(W, out=first), 5)
+    sets = [first] + [tuple(t.clone() for t in first) for _ in range(copies - 1)]
+    del W
+    res = {"N": N, "K": K, "bytes_per_block": 116, "quantize_us": round(q_ms * 1e3, 1),
+           "quantize_GBps": round((N * K * 4 + packed) / (q_ms * 1e-3) / 1e9, 1), "matmul": []}
+    for M in (1, 4, 16, 512):
+        X = activations(torch, gen, M, K)
+        ws = torch.empty(max(256, binding.itq3s_matmul_workspace_bytes(min(M, 16), N, K)), dtype=torch.uint8, device="cuda")
+        Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+
+        def run():
+            for c, sc, su in sets:
+                binding.itq3s_matmul_sub(c, sc, su, N, K, X, out=Y, workspace=ws)
+
+        ms = graph_time(torch, run, len(sets), reps=4 if M > 16 else 10)
+        row = {"M": M, "us": round(ms * 1e3, 2)}
+        if M <= 16:
+            row.update(GBps=round(packed / (ms * 1e-3) / 1e9, 1), frac_of_hbm_peak=round(packed / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4))
+        else:
+            row.update(TFLOPs=round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1))
+        res["matmul"].append(row)
     return res
 
 

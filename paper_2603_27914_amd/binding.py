@@ -379,15 +379,22 @@ def _need_subscales(subscales, codes, N, K):
         raise Itq3sError("subscales must be a contiguous int32 tensor of at least %d bytes on the device of codes" % nbytes)
 
 
-def itq3s_quantize_sub(W, status_flags=None):
-    """W: float32 [N, K] device tensor -> (codes, scales, subscales) int32 device tensors."""
+def itq3s_quantize_sub(W, out=None, status_flags=None):
+    """W: float32 [N, K] device tensor -> (codes, scales, subscales) int32 device tensors
+    (written into `out`, a triple from an earlier call on the same shape, if given)."""
     _need_cuda(W, status_flags)
     _need_flags(status_flags)
     if W.dtype != torch.float32 or W.dim() != 2 or W.stride(1) != 1:
         raise Itq3sError("W must be float32 [N, K] with unit column stride")
     N, K = W.shape
-    codes, scales = alloc_packed(N, K, W.device)
-    subscales = torch.empty(itq3s_subscales_bytes(N, K) // 4, dtype=torch.int32, device=W.device)
+    if out is not None:
+        codes, scales, subscales = out
+        _need_cuda(codes, scales, subscales)
+        _need_packed(codes, scales, N, K, subscales)
+        _need_subscales(subscales, codes, N, K)
+    else:
+        codes, scales = alloc_packed(N, K, W.device)
+        subscales = torch.empty(itq3s_subscales_bytes(N, K) // 4, dtype=torch.int32, device=W.device)
     _check(lib().itq3s_quantize_sub(_ptr(W), N, K, W.stride(0), _ptr(codes), _ptr(scales), _ptr(subscales), _ptr(status_flags), _stream()))
     return codes, scales, subscales
 
@@ -405,7 +412,7 @@ def itq3s_dequantize_sub(codes, scales, subscales, N, K, dtype=torch.float32, st
     return out
 
 
-def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, workspace=None, status_flags=None):
+def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, out=None, workspace=None, status_flags=None):
     """Y[M, N] = X[M, K] @ W_hat[N, K]^T from weights packed in the sub-block-scale variant.
     workspace: uint8 tensor of itq3s_matmul_workspace_bytes(min(M, 16), N, K) bytes for 5 <= M <= 64
     (allocated here if not given)."""
@@ -422,7 +429,12 @@ def itq3s_matmul_sub(codes, scales, subscales, N, K, X, dtype=torch.float32, wor
         workspace = torch.empty(itq3s_matmul_workspace_bytes(min(M, 16), N, K), dtype=torch.uint8, device=X.device)
     if workspace is not None and (workspace.dtype != torch.uint8 or not workspace.is_contiguous()):
         raise Itq3sError("workspace must be a contiguous uint8 tensor")
-    out = torch.empty((M, N), dtype=dtype, device=X.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=dtype, device=X.device)
+    elif not out.is_cuda or out.dtype not in (torch.float32, torch.float16) or tuple(out.shape) != (M, N) or out.stride(1) != 1:
+        raise Itq3sError("out must be a float32 or float16 [M, N] device tensor with unit column stride")
+    else:
+        dtype = out.dtype
     _check(lib().itq3s_matmul_sub(_ptr(codes), _ptr(scales), _ptr(subscales), N, K, _ptr(X), M, X.stride(0), _ptr(out), F16 if dtype == torch.float16 else F32,
                                   out.stride(0), _ptr(workspace), workspace.numel() if workspace is not None else 0, _ptr(status_flags), _stream()))
     return out

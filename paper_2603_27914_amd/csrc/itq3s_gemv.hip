@@ -166,7 +166,7 @@ template <int MP, int RT, bool kGrouped, int NBC, bool kSub = false, bool kRotat
 // (launch bounds: the second figure is a lower bound on wavefronts per SIMD: 4 = two workgroups per
 // compute unit = at most 128 registers, which every instantiation of the general pipeline meets
 // without scratch; the straight-line kernels use 57..92 registers on their own)
-__global__ __launch_bounds__(kGemvWaves * 64, (kSub && !kRotated) ? 2 : NBC > 0 ? 3 : 4) void gemv_kernel(const GemvArgs a) {
+__global__ __launch_bounds__(kGemvWaves * 64, NBC > 0 ? 3 : 4) void gemv_kernel(const GemvArgs a) {
     static_assert(!kRotated || (NBC == 0 && MP >= 8), "rotated activations: general pipeline");
     static_assert(kRotated || MP <= 4, "in-kernel rotation: at most four rows");
     static_assert(NSG == 1 || (NSG == 2 && kRotated), "row sub-groups: with rotated activations only");
