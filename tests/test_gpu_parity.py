@@ -336,6 +336,8 @@ GROUPS = [
     (1024, [200, 48], (33,)),                    # tiled path
     (2048, [300, 48, 1000], (20, 32, 300)),      # two passes of the streaming kernel; tiled path with split K and without
     (8192, [12304, 12304], (1,)),                # many row tiles per compute unit, the launch shape of 70B gate / up
+    (8192, [8192, 1024, 1024], (1,)),            # the q + k + v launch of the 70B step, as the benchmark launches it
+    (8192, [28672, 28672], (1,)),                # its gate + up launch
     (512, [5000, 4100], (2, 8, 16)),             # 570 row tiles: workgroups of two and three tiles, two row sub-groups for M >= 5
     (768, [9000], (5, 16)),                      # 563 row tiles, one tensor, ragged last tile
 ]
