@@ -44,3 +44,42 @@ def test_matmul_random_shapes_against_dequantize_and_dense_product(seed):
             err = ((got - want).norm(dim=1) / want.norm(dim=1).clamp_min(1e-300)).max().item()
             assert err <= tol, (M, N, K, dtype, err)
         done += 1
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_other_matmul_routes_on_random_shapes(seed):
+    """The same second route for the calls the test above does not reach: the weight-side kernel, the
+    static-scratch entry point, and the sub-block-scale variant on all three of its paths (fused
+    rotation, rotation launch, tiled weight-side kernel) against itq3s_dequantize_sub."""
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_27914_amd import binding
+
+    rng = np.random.default_rng(seed)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(200 + seed)
+
+    def rel(got, want):
+        return ((got.double() - want).norm(dim=1) / want.norm(dim=1).clamp_min(1e-300)).max().item()
+
+    done = 0
+    while done < 60:
+        K, N, M = 256 * int(rng.choice(KBS)), int(rng.choice(NS)), int(rng.choice(MS))
+        if N * K > 24e6 or M * K > 6e6:
+            continue
+        W = 0.02 * torch.randn((N, K), generator=g, device="cuda")
+        W[:, :: int(rng.choice([37, 64, 256]))] *= float(rng.choice([1.0, 4.0, 12.0]))  # uneven sub-blocks after the rotation
+        X = torch.randn((M, K), generator=g, device="cuda").to(torch.float16)
+        dtype = torch.float16 if rng.random() < 0.5 else torch.float32
+        codes, scales = binding.itq3s_quantize(W)
+        want = X.double() @ binding.itq3s_dequantize(codes, scales, N, K).double().T
+        assert rel(binding.itq3s_matmul_weight_side(codes, scales, N, K, X, dtype=dtype), want) <= 2e-3, ("weight side", M, N, K)
+        if binding.itq3s_matmul_workspace_bytes(M, N, K) <= (64 << 20):  # the static array's size
+            out = torch.empty((M, N), dtype=dtype, device="cuda")
+            assert rel(binding.itq3s_matmul_static(codes, scales, N, K, X, out), want) <= 2e-3, ("static", M, N, K)
+        c2, s2, u2 = binding.itq3s_quantize_sub(W)
+        want2 = X.double() @ binding.itq3s_dequantize_sub(c2, s2, u2, N, K).double().T
+        assert rel(binding.itq3s_matmul_sub(c2, s2, u2, N, K, X, dtype=dtype), want2) <= 2e-3, ("sub", M, N, K)
+        done += 1
