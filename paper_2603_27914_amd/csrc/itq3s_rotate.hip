@@ -20,7 +20,8 @@ namespace itq3s {
 // elements e = 64 (l/16) + 16 i + l%16, i = 0..3.
 // Returns false if a rotated value (or the intermediate T, which then turns the result into NaN)
 // leaves the fp16 range.
-__device__ __forceinline__ bool rotate_chunk(const _Float16* __restrict__ src, int lane, _Float16 out[4]) {
+// `first` receives x[16 (l%16) + 4 (l/16)], the first of the lane's four inputs (lane 0: x[0]).
+__device__ __forceinline__ bool rotate_chunk(const _Float16* __restrict__ src, int lane, _Float16 out[4], _Float16* first = nullptr) {
     const int r16 = lane & 15, g = lane >> 4;
     half4 h, q;  // H_16[4g + j][r16] and a quarter of it
 #pragma unroll
@@ -30,6 +31,7 @@ __device__ __forceinline__ bool rotate_chunk(const _Float16* __restrict__ src, i
         q[j] = neg ? (_Float16)(-0.25f) : (_Float16)0.25f;
     }
     const half4 xa = *reinterpret_cast<const half4*>(src + 16 * r16 + 4 * g);
+    if (first != nullptr) *first = xa[0];
     const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
     const floatx4 T = __builtin_amdgcn_mfma_f32_16x16x16f16(xa, q, zero, 0, 0, 0);
     half4 th, tl;
@@ -60,20 +62,29 @@ __device__ __forceinline__ bool rotate_chunk(const _Float16* __restrict__ src, i
 // every one of them out)
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void rotate_frag_kernel(const _Float16* __restrict__ X, int64_t M, int64_t K, int64_t ldx, int MP,
                                                           _Float16* __restrict__ Xt, float* __restrict__ S, uint32_t* __restrict__ flags) {
-    const int64_t KB = K / kBlock;
+    const int KB = (int)(K / kBlock);
     const int lane = lane_id();
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // m * KB + b over MP rows
-    if (chunk >= (int64_t)MP * KB) return;
-    const int64_t m = chunk / KB, b = chunk - m * KB;
+    // (32-bit, wave-uniform index arithmetic: MP * KB chunks, far below 2^31)
+    const int chunk = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // m * KB + b over MP rows
+    if (chunk >= MP * KB) return;
+    const int m = chunk / KB, b = chunk - m * KB;
     _Float16 r[4] = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
-    if (m < M && !rotate_chunk(X + m * ldx + b * kBlock, lane, r) && flags != nullptr) atomicOr(flags, kFlagActRange);
+    _Float16 x0 = (_Float16)0.f;
+    if (m < M && !rotate_chunk(X + (int64_t)m * ldx + (int64_t)b * kBlock, lane, r, &x0) && flags != nullptr) atomicOr(flags, kFlagActRange);
+    // sum of the rounded chunk: inside a row of 16 lanes through the crossbar, the four rows through scalar registers
     float s = ((float)r[0] + (float)r[1]) + ((float)r[2] + (float)r[3]);
-#pragma unroll
-    for (int k = 1; k < 64; k <<= 1) s += xor_lane_f32(s, k);
+    s += __builtin_bit_cast(float, row_xor_i32<1>(__builtin_bit_cast(int, s)));
+    s += __builtin_bit_cast(float, row_xor_i32<2>(__builtin_bit_cast(int, s)));
+    s += __builtin_bit_cast(float, row_xor_i32<4>(__builtin_bit_cast(int, s)));
+    s += __builtin_bit_cast(float, row_xor_i32<8>(__builtin_bit_cast(int, s)));
+    const float total = (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 0)) +
+                         __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 16))) +
+                        (__builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 32)) +
+                         __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, s), 48)));
     if (lane == 0) {
-        S[b * MP + m] = s;
-        // exact sum of the unrounded chunk: H 1 = 16 e_0
-        S[KB * MP + b * MP + m] = m < M ? 16.0f * (float)X[m * ldx + b * kBlock] : 0.f;
+        S[b * MP + m] = total;
+        // exact sum of the unrounded chunk: H 1 = 16 e_0 (lane 0 holds x[0] from its operand load)
+        S[KB * MP + b * MP + m] = 16.0f * (float)x0;
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -81,7 +92,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
         const int g = e >> 6, w = (e >> 4) & 3, slot = e & 15;
         const int t = 2 * w + ((slot & 7) >> 2);
         const int i = 2 * (slot & 3) + (slot >> 3);
-        Xt[((((b * 8 + t) * 4 + g) * MP + m) * 8) + i] = r[j];
+        Xt[(((((int64_t)b * 8 + t) * 4 + g) * MP + m) * 8) + i] = r[j];
     }
 }
 
